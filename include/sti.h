@@ -1,0 +1,188 @@
+/*
+ * sti.h - C ABI of the shard-decode + shard-subset encoder-layer library for
+ * AMD MI355X (gfx950).
+ *
+ * The library executes the compute side of the paper's inference pipeline:
+ * a model is stored as N x M x K shard versions (layer, vertical slice,
+ * bitwidth; Section "storing shards per version"); a submodel selects, per
+ * layer, a subset of the M shards and one fidelity version of each (Section
+ * "vertical partitioning", "quantization per shard"); a layer is decompressed
+ * and computed as one job and layers run in order (Section "Submodel
+ * execution").  Biases and LayerNorm parameters are not part of shards and
+ * stay resident in full precision (Section "Implementation", last paragraph).
+ * Embeddings, pooler and task heads are outside this library.
+ *
+ * Conventions for every entry point
+ * ---------------------------------
+ *  - Pointers marked DEVICE are device (HBM) addresses owned by the caller;
+ *    pointers marked HOST are ordinary host memory that is read only during
+ *    the call and may be freed as soon as it returns.
+ *  - `hip_stream` is a hipStream_t (NULL = the default stream).  All device
+ *    work is enqueued on it; no entry point synchronises the device.  Results
+ *    are valid once the stream has reached the end of the enqueued work.
+ *  - Nothing is thrown or aborted across the ABI: the return code is the only
+ *    error channel.  All argument validation happens before the first launch,
+ *    so an argument error leaves the outputs untouched.
+ *  - The library allocates no device memory.  Scratch space comes in through
+ *    the `workspace` arguments; the only state it keeps is a small pinned host
+ *    staging ring used to upload shard tables.  Two calls that are given the
+ *    same workspace must be ordered (same stream, or caller-side events).
+ *  - The call fails with STI_ERR_HIP when no gfx950 device code can run.
+ *
+ * Stream format of a k-bit shard (k = 2..6)
+ * -----------------------------------------
+ *  Index j of the shard occupies bits [j*k, j*k + k) of a gap-free bitstream;
+ *  stream bit b is bit (b mod 8) of byte floor(b / 8) (least significant bit
+ *  first; the two 4-bit indexes of a byte are low nibble first).  There is no
+ *  per-row padding.  The stream is ceil(n*k/8) bytes and must start on a
+ *  16-byte boundary.  A 32-bit shard is n raw float32 values.
+ *
+ * Logical layout of the decoded weights of a shard (Table 1)
+ * ----------------------------------------------------------
+ *  Six row-major [out_features][in_features] sub-blocks, in this order:
+ *    Wq [dh x d]  Wk [dh x d]  Wv [dh x d]   rows of the layer's Q/K/V matrices of head i
+ *    Wo [d x dh]                             columns of the output projection reading head i
+ *    W1 [f x d]                              rows i*f .. (i+1)*f of FFN1
+ *    W2 [d x f]                              columns i*f .. (i+1)*f of FFN2
+ *  with d = d_model, dh = d_head, f = ffn_per_shard; d*(4*dh + 2*f) weights.
+ */
+#ifndef STI_H
+#define STI_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    STI_OK = 0,
+    STI_ERR_NULL = 1,          /* a required pointer is NULL                               */
+    STI_ERR_DIMS = 2,          /* a size is negative, zero where it may not be, or unsupported */
+    STI_ERR_BITWIDTH = 3,      /* bitwidth outside {0, 2, 3, 4, 5, 6, 32} (0 only where absent is allowed) */
+    STI_ERR_MISSING_SHARD = 4, /* the plan selects a version whose data pointer is NULL    */
+    STI_ERR_ALIGN = 5,         /* a device pointer is not aligned as documented            */
+    STI_ERR_WORKSPACE = 6,     /* workspace NULL or smaller than the query function says   */
+    STI_ERR_DTYPE = 7,         /* unknown sti_dtype / sti_precision value                  */
+    STI_ERR_HIP = 8,           /* a HIP runtime call failed (launch, copy, event)          */
+    STI_ERR_UNSUPPORTED = 9    /* valid request that this build does not implement         */
+} sti_status;
+
+typedef enum { STI_F32 = 0, STI_F16 = 1, STI_BF16 = 2 } sti_dtype;
+
+/* STI_PREC_F32: float32 storage and arithmetic end to end (decode to a float32
+ *   working buffer, then float32 kernels); any dimensions.
+ * STI_PREC_F16_MFMA: binary16 operands on the matrix cores with float32
+ *   accumulation, decode fused into the weight loader; needs d_model, d_head
+ *   and ffn_per_shard to be multiples of 64 and seq <= 512. */
+typedef enum { STI_PREC_F32 = 0, STI_PREC_F16_MFMA = 1 } sti_precision;
+
+typedef struct {
+    int32_t d_model;       /* d  : hidden size                                   */
+    int32_t n_heads;       /* M  : attention heads = shards per layer (<= 64)    */
+    int32_t d_head;        /* dh : features per head (d_model need not equal M*dh) */
+    int32_t ffn_per_shard; /* f  : FFN neurons per shard (d_ff / M)              */
+    float ln_eps;          /* LayerNorm epsilon (BERT uses 1e-12)                */
+} sti_dims;
+
+/* One fidelity version of one shard (Figure "instantiating N x M x K model
+ * shards": k-bit index matrix + centroid dictionary + outlier dictionary). */
+typedef struct {
+    int8_t bitwidth;             /* 0 = absent, 2..6 = packed indexes, 32 = raw float32          */
+    const void *data;            /* DEVICE. ceil(n*k/8) bytes or n float32; 16-byte aligned      */
+    const float *codebook;       /* DEVICE. 2^k float32 centroids, 4-byte aligned; ignored for 32 */
+    uint32_t n_outliers;         /* reserved for the outlier dictionary; must be 0               */
+    const uint32_t *outlier_pos; /* reserved; must be NULL                                       */
+    const float *outlier_val;    /* reserved; must be NULL                                       */
+} sti_shard;
+
+/* Resident full-precision parameters of one layer.  All DEVICE float32. */
+typedef struct {
+    const float *bq, *bk, *bv; /* [M*dh]  biases of the Q/K/V projections, head-major      */
+    const float *bo;           /* [d]     bias of the output projection                    */
+    const float *b1;           /* [M*f]   bias of FFN1, slice-major                        */
+    const float *b2;           /* [d]     bias of FFN2                                     */
+    const float *ln1_g, *ln1_b; /* [d]    LayerNorm after the attention block              */
+    const float *ln2_g, *ln2_b; /* [d]    LayerNorm after the feed-forward block           */
+} sti_layer_params;
+
+/* Text for a status code (static storage, never NULL). */
+const char *sti_status_string(sti_status s);
+
+/* ---------------------------------------------------------------------------
+ * Decompression (Section "quantization per shard": "substituting dictionary
+ * indexes with floating point centroids"; Section "Implementation": the
+ * index -> centroid substitution loop).
+ *
+ * For s in [0, n_shards), j in [0, weights_per_shard):
+ *     out[s*weights_per_shard + j] = round_to(out_dtype, codebook_s[index_s[j]])
+ * or the raw value for a 32-bit shard.  Rounding to F16/BF16 is to nearest,
+ * ties to even, subnormals kept, overflow to infinity; F32 output is the
+ * centroid bit for bit.
+ *
+ *  shards            HOST array [n_shards]; bitwidth 0 is NOT allowed here.
+ *  weights_per_shard number of weights n of every shard (any value >= 0).
+ *  out               DEVICE, n_shards*n elements of out_dtype, 16-byte aligned.
+ *  workspace         DEVICE scratch of at least sti_decode_workspace_bytes(n_shards)
+ *                    bytes, 16-byte aligned; may be NULL when that size is 0.
+ *
+ * Errors: NULL / DIMS (negative counts) / BITWIDTH / MISSING_SHARD (data NULL,
+ * or codebook NULL for k <= 6) / ALIGN / WORKSPACE / DTYPE / UNSUPPORTED
+ * (n_outliers != 0) / HIP.
+ * ------------------------------------------------------------------------- */
+size_t sti_decode_workspace_bytes(int n_shards);
+
+sti_status sti_decode_shards(const sti_shard *shards, int n_shards, uint64_t weights_per_shard,
+                             void *out, sti_dtype out_dtype, void *workspace,
+                             size_t workspace_bytes, void *hip_stream);
+
+/* ---------------------------------------------------------------------------
+ * One encoder layer over a shard subset (Section "A primer on transformer":
+ * per-head Q, K, V -> attention scores -> output projection O -> two FFN
+ * linears; Section "vertical partitioning": any subset of a layer's shards
+ * executes; Table 1).  With P the present shards and X the input [B*L x d]:
+ *
+ *   Q_i = X Wq_i^T + bq_i (same K_i, V_i);  C_i = softmax(Q_i K_i^T / sqrt(dh)) V_i  per sequence
+ *   h   = LayerNorm1( X + bo + sum_{i in P} C_i Wo_i^T )
+ *   U_i = gelu( h W1_i^T + b1_i ),  gelu(z) = z/2 (1 + erf(z / sqrt 2))
+ *   y   = LayerNorm2( h + b2 + sum_{i in P} U_i W2_i^T )
+ *
+ * LayerNorm uses the biased variance over d and ln_eps.  An absent shard adds
+ * nothing and nothing is rescaled; a layer with every shard absent is valid.
+ *
+ *  shards   HOST array [M]; bitwidth 0 = absent.
+ *  params   HOST struct of DEVICE pointers.
+ *  x, y     DEVICE [batch][seq][d_model] of io_dtype, 16-byte aligned, not aliased.
+ *  workspace DEVICE, >= sti_workspace_bytes(dims, batch, seq, precision), 256-byte aligned.
+ *
+ * sti_workspace_bytes returns 0 for invalid arguments.
+ * ------------------------------------------------------------------------- */
+size_t sti_workspace_bytes(const sti_dims *dims, int batch, int seq, sti_precision precision);
+
+sti_status sti_layer_forward(const sti_dims *dims, const sti_shard *shards,
+                             const sti_layer_params *params, const void *x, void *y,
+                             sti_dtype io_dtype, int batch, int seq, sti_precision precision,
+                             void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* ---------------------------------------------------------------------------
+ * Layers 0 .. n_layers-1 in order, the output of one feeding the next (Section
+ * "Submodel execution").  A shallower submodel is run by passing fewer layers.
+ *
+ *  store   HOST array [n_layers][M][6]: the versions of shard (l, i) for
+ *          k = 2, 3, 4, 5, 6, 32 in that order; data == NULL where a version is
+ *          not stored.  The bitwidth field of a stored version must match its slot.
+ *  params  HOST array [n_layers].
+ *  plan    HOST int8 [n_layers][M]: 0 = absent, else the bitwidth to use.
+ *  x, y    as for sti_layer_forward; n_layers == 0 copies x to y.
+ * ------------------------------------------------------------------------- */
+sti_status sti_model_forward(const sti_dims *dims, int n_layers, const sti_shard *store,
+                             const sti_layer_params *params, const int8_t *plan, const void *x,
+                             void *y, sti_dtype io_dtype, int batch, int seq,
+                             sti_precision precision, void *workspace, size_t workspace_bytes,
+                             void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* STI_H */

@@ -1,0 +1,12 @@
+"""Python binding of libsti (MI355X / gfx950 shard decode + encoder layer).
+
+Argument marshalling only: every step of the path runs in the HIP kernels of
+``libsti.so``.  Importing this package fails loudly when the library has not
+been built (``python -m paper_2207_05022_amd.build``); there is no fallback.
+"""
+from .binding import (  # noqa: F401
+    STI_F32, STI_F16, STI_BF16, STI_PREC_F32, STI_PREC_F16_MFMA,
+    StiError, StiDims, StiShard, StiLayerParams, lib, status_string,
+    sti_decode_workspace_bytes, sti_decode_shards, sti_workspace_bytes,
+    sti_layer_forward, sti_model_forward,
+)

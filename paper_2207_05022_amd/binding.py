@@ -1,0 +1,198 @@
+"""ctypes marshalling for the C ABI declared in include/sti.h.
+
+Device buffers are ``torch`` CUDA tensors (PyTorch-ROCm is used only to own
+device memory and streams); their ``data_ptr()`` and the current stream's
+handle are what crosses the boundary.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libsti.so")
+
+STI_F32, STI_F16, STI_BF16 = 0, 1, 2
+STI_PREC_F32, STI_PREC_F16_MFMA = 0, 1
+VERSION_SLOTS = (2, 3, 4, 5, 6, 32)
+
+
+class StiDims(C.Structure):
+    _fields_ = [("d_model", C.c_int32), ("n_heads", C.c_int32), ("d_head", C.c_int32),
+                ("ffn_per_shard", C.c_int32), ("ln_eps", C.c_float)]
+
+
+class StiShard(C.Structure):
+    _fields_ = [("bitwidth", C.c_int8), ("data", C.c_void_p), ("codebook", C.c_void_p),
+                ("n_outliers", C.c_uint32), ("outlier_pos", C.c_void_p),
+                ("outlier_val", C.c_void_p)]
+
+
+class StiLayerParams(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in
+                ("bq", "bk", "bv", "bo", "b1", "b2", "ln1_g", "ln1_b", "ln2_g", "ln2_b")]
+
+
+class StiError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: status {status} ({status_string(status)})")
+
+
+def _load():
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            f"{LIB_PATH} is missing: build the HIP library first "
+            "(python -m paper_2207_05022_amd.build); there is no CPU fallback")
+    L = C.CDLL(LIB_PATH)
+    L.sti_status_string.restype = C.c_char_p
+    L.sti_status_string.argtypes = [C.c_int]
+    L.sti_decode_workspace_bytes.restype = C.c_size_t
+    L.sti_decode_workspace_bytes.argtypes = [C.c_int]
+    L.sti_decode_shards.restype = C.c_int
+    L.sti_decode_shards.argtypes = [C.POINTER(StiShard), C.c_int, C.c_uint64, C.c_void_p, C.c_int,
+                                    C.c_void_p, C.c_size_t, C.c_void_p]
+    if hasattr(L, "sti_workspace_bytes"):
+        L.sti_workspace_bytes.restype = C.c_size_t
+        L.sti_workspace_bytes.argtypes = [C.POINTER(StiDims), C.c_int, C.c_int, C.c_int]
+        L.sti_layer_forward.restype = C.c_int
+        L.sti_layer_forward.argtypes = [
+            C.POINTER(StiDims), C.POINTER(StiShard), C.POINTER(StiLayerParams), C.c_void_p,
+            C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.sti_model_forward.restype = C.c_int
+        L.sti_model_forward.argtypes = [
+            C.POINTER(StiDims), C.c_int, C.POINTER(StiShard), C.POINTER(StiLayerParams),
+            C.POINTER(C.c_int8), C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int,
+            C.c_void_p, C.c_size_t, C.c_void_p]
+    return L
+
+
+lib = _load()
+
+
+def status_string(status: int) -> str:
+    return lib.sti_status_string(int(status)).decode()
+
+
+def _dtype_code(t) -> int:
+    import torch
+    return {torch.float32: STI_F32, torch.float16: STI_F16, torch.bfloat16: STI_BF16}[t.dtype]
+
+
+def _stream_handle(stream) -> Optional[int]:
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return C.c_void_p(stream.cuda_stream)
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def make_dims(dims) -> StiDims:
+    """dims: any object with d_model, n_heads, d_head, ffn_per_shard, ln_eps."""
+    if isinstance(dims, StiDims):
+        return dims
+    return StiDims(dims.d_model, dims.n_heads, dims.d_head, dims.ffn_per_shard, dims.ln_eps)
+
+
+def make_shard(bitwidth: int, data=None, codebook=None) -> StiShard:
+    """data / codebook: CUDA tensors (uint8 stream or float32 weights; float32 centroids)."""
+    return StiShard(int(bitwidth), _ptr(data), _ptr(codebook), 0, None, None)
+
+
+def make_params(p) -> StiLayerParams:
+    """p: object with CUDA float32 tensors bq, bk, bv, bo, b1, b2, ln1_g, ln1_b, ln2_g, ln2_b."""
+    if isinstance(p, StiLayerParams):
+        return p
+    return StiLayerParams(*[_ptr(getattr(p, n)) for n, _ in StiLayerParams._fields_])
+
+
+def _shard_array(shards: Sequence) -> "C.Array":
+    if isinstance(shards, C.Array):
+        return shards
+    arr = (StiShard * max(1, len(shards)))()
+    for i, s in enumerate(shards):
+        if s is None:
+            arr[i] = StiShard(0, None, None, 0, None, None)
+        elif isinstance(s, StiShard):
+            arr[i] = s
+        else:
+            arr[i] = make_shard(s.bitwidth, s.data, s.codebook)
+    return arr
+
+
+def sti_decode_workspace_bytes(n_shards: int) -> int:
+    return int(lib.sti_decode_workspace_bytes(int(n_shards)))
+
+
+def sti_decode_shards(shards: Sequence, weights_per_shard: int, out, workspace=None,
+                      stream=None) -> None:
+    """Decode ``shards`` into ``out`` (CUDA tensor of float32/float16/bfloat16 with
+    len(shards) * weights_per_shard elements)."""
+    arr = _shard_array(shards)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    st = lib.sti_decode_shards(arr, len(shards), int(weights_per_shard), _ptr(out),
+                               _dtype_code(out), _ptr(workspace), ws_bytes, _stream_handle(stream))
+    if st != 0:
+        raise StiError(st, "sti_decode_shards")
+
+
+def sti_workspace_bytes(dims, batch: int, seq: int, precision: int) -> int:
+    d = make_dims(dims)
+    return int(lib.sti_workspace_bytes(C.byref(d), int(batch), int(seq), int(precision)))
+
+
+def sti_layer_forward(dims, shards: Sequence, params, x, y, precision: int, workspace,
+                      stream=None) -> None:
+    """x, y: CUDA tensors [batch, seq, d_model] of one dtype; shards: M entries, None = absent."""
+    d = make_dims(dims)
+    arr = _shard_array(shards)
+    p = make_params(params)
+    batch, seq = int(x.shape[0]), int(x.shape[1])
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    st = lib.sti_layer_forward(C.byref(d), arr, C.byref(p), _ptr(x), _ptr(y), _dtype_code(x),
+                               batch, seq, int(precision), _ptr(workspace), ws_bytes,
+                               _stream_handle(stream))
+    if st != 0:
+        raise StiError(st, "sti_layer_forward")
+
+
+def make_store(store_rows: Sequence[Sequence[dict]]) -> "C.Array":
+    """store_rows[l][i]: dict bitwidth -> shard object (.bitwidth/.data/.codebook CUDA tensors)."""
+    n_layers = len(store_rows)
+    M = len(store_rows[0]) if n_layers else 0
+    arr = (StiShard * max(1, n_layers * M * 6))()
+    for l, row in enumerate(store_rows):
+        for i, versions in enumerate(row):
+            for v, k in enumerate(VERSION_SLOTS):
+                s = versions.get(k) if versions else None
+                idx = (l * M + i) * 6 + v
+                arr[idx] = (make_shard(k, s.data, s.codebook) if s is not None
+                            else StiShard(k, None, None, 0, None, None))
+    return arr
+
+
+def sti_model_forward(dims, store, params: Sequence, plan, x, y, precision: int, workspace,
+                      stream=None) -> None:
+    """store: result of make_store (or a ctypes StiShard array [n_layers][M][6]);
+    plan: int8 numpy array [n_layers][M]."""
+    import numpy as np
+    d = make_dims(dims)
+    plan = np.ascontiguousarray(plan, dtype=np.int8)
+    n_layers = int(plan.shape[0]) if plan.ndim == 2 else 0
+    if not isinstance(store, C.Array):
+        store = make_store(store)
+    ps = (StiLayerParams * max(1, n_layers))()
+    for l in range(n_layers):
+        ps[l] = make_params(params[l])
+    batch, seq = int(x.shape[0]), int(x.shape[1])
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    st = lib.sti_model_forward(C.byref(d), n_layers, store, ps,
+                               plan.ctypes.data_as(C.POINTER(C.c_int8)), _ptr(x), _ptr(y),
+                               _dtype_code(x), batch, seq, int(precision), _ptr(workspace),
+                               ws_bytes, _stream_handle(stream))
+    if st != 0:
+        raise StiError(st, "sti_model_forward")

@@ -1,0 +1,44 @@
+"""Upload helpers: host (numpy) shards and parameters -> CUDA tensors.
+
+Plumbing only.  Streams are copied through one pooled allocation per call so
+that every shard starts on a 256-byte boundary.
+"""
+from __future__ import annotations
+
+from types import SimpleNamespace
+from typing import List, Optional, Sequence
+
+import numpy as np
+import torch
+
+
+def upload_shard(sh, device="cuda"):
+    """sh: object with bitwidth, data (numpy uint8 / float32), codebook (numpy float32 or None)."""
+    if sh is None:
+        return None
+    if sh.bitwidth == 32:
+        data = torch.from_numpy(np.ascontiguousarray(sh.data, dtype=np.float32)).to(device)
+        cb = None
+    else:
+        data = torch.from_numpy(np.ascontiguousarray(sh.data, dtype=np.uint8)).to(device)
+        cb = torch.from_numpy(np.ascontiguousarray(sh.codebook, dtype=np.float32)).to(device)
+    return SimpleNamespace(bitwidth=int(sh.bitwidth), data=data, codebook=cb)
+
+
+def upload_params(p, device="cuda"):
+    names = ("bq", "bk", "bv", "bo", "b1", "b2", "ln1_g", "ln1_b", "ln2_g", "ln2_b")
+    return SimpleNamespace(**{n: torch.from_numpy(np.ascontiguousarray(getattr(p, n), dtype=np.float32)).to(device)
+                              for n in names})
+
+
+def upload_workload(wl, device="cuda"):
+    """Returns (shards [n_layers][M] with None = absent, params [n_layers], x tensor)."""
+    shards = [[upload_shard(s, device) for s in row] for row in wl.shards]
+    params = [upload_params(p, device) for p in wl.params]
+    x = torch.from_numpy(np.ascontiguousarray(wl.x)).to(device)
+    return shards, params, x
+
+
+def store_from_plan(shards) -> List[List[dict]]:
+    """Version store holding exactly the versions a workload's plan uses."""
+    return [[({s.bitwidth: s} if s is not None else {}) for s in row] for row in shards]

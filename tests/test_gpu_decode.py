@@ -1,0 +1,104 @@
+"""GPU parity: sti_decode_shards (through the C ABI) against the CPU oracle, bit for bit."""
+import numpy as np
+import pytest
+
+import sti_synth as S
+
+pytestmark = pytest.mark.gpu
+
+DT = {"f32": ("float32", 0), "f16": ("float16", 1), "bf16": ("bfloat16", 2)}
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    import paper_2207_05022_amd as P
+    from paper_2207_05022_amd import device as D
+    assert torch.cuda.is_available(), "needs a GPU"
+    return torch, P, D
+
+
+def run_decode(gpu, shards, n, dtype):
+    torch, P, D = gpu
+    dev = [D.upload_shard(s) for s in shards]
+    out = torch.full((len(shards) * n,), 7, dtype=getattr(torch, DT[dtype][0]), device="cuda")
+    ws_bytes = P.sti_decode_workspace_bytes(len(shards))
+    ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device="cuda")
+    P.sti_decode_shards(dev, n, out, ws)
+    torch.cuda.synchronize()
+    if dtype == "f32":
+        return out.view(torch.int32).cpu().numpy().view(np.uint32).reshape(len(shards), n)
+    return out.view(torch.int16).cpu().numpy().view(np.uint16).reshape(len(shards), n)
+
+
+def oracle_bits(oracle_mod, shards, n, dtype):
+    out = oracle_mod.decode_shards(shards, n, DT[dtype][1])
+    return out.view(np.uint32) if dtype == "f32" else out
+
+
+@pytest.mark.parametrize("dtype", ["f16", "f32", "bf16"])
+@pytest.mark.parametrize("n", [589824, 16384 * 3 + 8 * 5, 8 * 2048 + 24])
+def test_each_bitwidth_whole_units(gpu, oracle_mod, dtype, n):
+    rng = np.random.default_rng(n % 1000 + len(dtype))
+    shards = [S.make_shard(rng, n, k) for k in (2, 3, 4, 5, 6, 32)]
+    got = run_decode(gpu, shards, n, dtype)
+    want = oracle_bits(oracle_mod, shards, n, dtype)
+    assert np.array_equal(got, want)
+
+
+@pytest.mark.parametrize("dtype", ["f16", "f32"])
+@pytest.mark.parametrize("n", [1, 3, 7, 9, 31, 1001, 16384 + 5, 40003])
+def test_ragged_sizes(gpu, oracle_mod, dtype, n):
+    rng = np.random.default_rng(n)
+    shards = [S.make_shard(rng, n, k) for k in (2, 3, 4, 5, 6, 32, 5, 3)]
+    got = run_decode(gpu, shards, n, dtype)
+    want = oracle_bits(oracle_mod, shards, n, dtype)
+    assert np.array_equal(got, want)
+
+
+def test_many_shards_use_the_device_table(gpu, oracle_mod):
+    n = 4096 + 64
+    rng = np.random.default_rng(77)
+    ks = rng.choice([2, 3, 4, 5, 6, 32], size=150)
+    shards = [S.make_shard(rng, n, int(k)) for k in ks]
+    got = run_decode(gpu, shards, n, "f16")
+    want = oracle_bits(oracle_mod, shards, n, "f16")
+    assert np.array_equal(got, want)
+
+
+def test_bert_large_shaped_shard(gpu, oracle_mod):
+    n = S.BERT_LARGE_SHAPED.weights_per_shard
+    rng = np.random.default_rng(3)
+    shards = [S.make_shard(rng, n, k) for k in (3, 6)]
+    got = run_decode(gpu, shards, n, "f16")
+    assert np.array_equal(got, oracle_bits(oracle_mod, shards, n, "f16"))
+
+
+def test_special_values_round_like_the_oracle(gpu, oracle_mod):
+    vals = np.array([0.0, -0.0, np.inf, -np.inf, 65504.0, 65519.9, 65520.0, 1e10, 2.0 ** -14,
+                     2.0 ** -24, 2.0 ** -25, 2.0 ** -25 * 1.0001, 2.0 ** -26, 1e-30, 1e-45,
+                     1.0 + 2.0 ** -11, 1.0 + 3 * 2.0 ** -11, 3.3895314e38, 0.1, -1 / 3,
+                     6.0e-5, 5.96e-8, 2.98e-8, 1.0009765625, 1.00048828125], dtype=np.float32)
+    nan_bits = np.array([0x7FC00000, 0xFFC00000, 0x7F800001, 0x7FA00000], dtype=np.uint32)
+    vals = np.concatenate([vals, nan_bits.view(np.float32)])
+    # as a raw 32-bit shard and as the codebook of a 5-bit shard (32 entries)
+    n = vals.size
+    raw = S.Shard(32, vals, None)
+    cb = np.resize(vals, 32).astype(np.float32)
+    idx_stream = np.random.default_rng(1).integers(0, 256, size=5 * 64, dtype=np.uint8)
+    packed = S.Shard(5, idx_stream, cb)
+    for dtype in ("f16", "bf16", "f32"):
+        got = run_decode(gpu, [raw], n, dtype)
+        assert np.array_equal(got, oracle_bits(oracle_mod, [raw], n, dtype)), dtype
+        got = run_decode(gpu, [packed], 512, dtype)
+        assert np.array_equal(got, oracle_bits(oracle_mod, [packed], 512, dtype)), dtype
+
+
+def test_empty_inputs(gpu):
+    torch, P, D = gpu
+    out = torch.zeros(8, dtype=torch.float16, device="cuda")
+    P.sti_decode_shards([], 100, out, None)
+    sh = D.upload_shard(S.make_shard(np.random.default_rng(0), 64, 4))
+    P.sti_decode_shards([sh], 0, out, None)
+    torch.cuda.synchronize()
+    assert float(out.abs().sum()) == 0.0
