@@ -81,6 +81,186 @@ sti_status check_decode_shard(const sti_shard &s)
     return STI_OK;
 }
 
+
+// ---------------------------------------------------------------------------
+// Layer sequencing
+// ---------------------------------------------------------------------------
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+struct WorkspaceLayout {
+    size_t w32 = 0, act[2] = {0, 0}, qkv = 0, ctx = 0, pre = 0, h = 0, u = 0, total = 0;
+};
+
+// Offsets of the scratch regions of one layer call (sized for all M shards present).
+WorkspaceLayout workspace_layout(const sti_dims &d, int64_t T, sti_precision prec)
+{
+    WorkspaceLayout L;
+    const size_t es = (prec == STI_PREC_F32) ? 4 : 2;
+    const size_t M = d.n_heads, dm = d.d_model, dh = d.d_head, f = d.ffn_per_shard;
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        size_t at = off;
+        off = align_up(off + bytes, 256);
+        return at;
+    };
+    if (prec == STI_PREC_F32) L.w32 = take(M * dm * (4 * dh + 2 * f) * 4);
+    L.act[0] = take((size_t)T * dm * es);
+    L.act[1] = take((size_t)T * dm * es);
+    L.qkv = take((size_t)T * M * 3 * dh * es);
+    L.ctx = take((size_t)T * M * dh * es);
+    L.pre = take((size_t)T * dm * 4);
+    L.h = take((size_t)T * dm * es);
+    L.u = take((size_t)T * M * f * es);
+    L.total = off;
+    return L;
+}
+
+sti_status check_dims(const sti_dims *dims, int batch, int seq, sti_precision prec)
+{
+    if (!dims) return STI_ERR_NULL;
+    if (prec != STI_PREC_F32 && prec != STI_PREC_F16_MFMA) return STI_ERR_DTYPE;
+    if (dims->d_model <= 0 || dims->d_head <= 0 || dims->ffn_per_shard <= 0) return STI_ERR_DIMS;
+    if (dims->n_heads <= 0 || dims->n_heads > kMaxShardsPerLayer) return STI_ERR_DIMS;
+    if (!(dims->ln_eps >= 0.0f)) return STI_ERR_DIMS;
+    if (batch < 0 || seq < 0) return STI_ERR_DIMS;
+    if (dims->d_model > (1 << 16) || dims->d_head > (1 << 12) || dims->ffn_per_shard > (1 << 16))
+        return STI_ERR_DIMS;
+    if ((int64_t)batch * seq > (1 << 24) || batch > 65535) return STI_ERR_DIMS;
+    if (prec == STI_PREC_F32) {
+        // the float32 attention kernel keeps one score row per wave in LDS
+        if ((size_t)4 * ((size_t)seq + dims->d_head) * 4 > 65536) return STI_ERR_DIMS;
+    } else {
+        if (dims->d_model % 64 || dims->ffn_per_shard % 64) return STI_ERR_DIMS;
+        if (dims->d_head != 64) return STI_ERR_DIMS;
+        if (seq > 512) return STI_ERR_DIMS;
+    }
+    return STI_OK;
+}
+
+sti_status check_layer_shard(const sti_shard &s)
+{
+    if (s.bitwidth == 0) return STI_OK;
+    return check_decode_shard(s);
+}
+
+sti_status check_params(const sti_layer_params *p)
+{
+    if (!p) return STI_ERR_NULL;
+    const float *all[10] = {p->bq, p->bk, p->bv, p->bo, p->b1, p->b2,
+                            p->ln1_g, p->ln1_b, p->ln2_g, p->ln2_b};
+    for (const float *q : all) {
+        if (!q) return STI_ERR_NULL;
+        if (!aligned(q, 4)) return STI_ERR_ALIGN;
+    }
+    return STI_OK;
+}
+
+inline const void *block_start(const sti_shard &s, size_t elem_off)
+{
+    if (s.bitwidth == 32) return (const float *)s.data + elem_off;
+    return (const uint8_t *)s.data + elem_off * (size_t)s.bitwidth / 8;
+}
+
+#define STI_TRY(expr)                          \
+    do {                                       \
+        if ((expr) != hipSuccess) return STI_ERR_HIP; \
+    } while (0)
+
+// One layer, arguments already validated.  `in` is float32 (F32 precision) or
+// binary16 (MFMA precision); `out` is written as out_dtype.
+sti_status run_layer(const sti_dims &d, const sti_shard *shards, const sti_layer_params &prm,
+                     const void *in, void *out, sti_dtype out_dtype, int B, int Lseq,
+                     sti_precision prec, uint8_t *ws, const WorkspaceLayout &wl, hipStream_t stream)
+{
+    const int dm = d.d_model, M = d.n_heads, dh = d.d_head, f = d.ffn_per_shard;
+    const int T = B * Lseq;
+    if (T == 0) return STI_OK;
+    const size_t wsh = (size_t)dm * (4 * dh + 2 * f);
+    const size_t off_o = (size_t)3 * dh * dm, off_1 = (size_t)4 * dh * dm,
+                 off_2 = (size_t)4 * dh * dm + (size_t)f * dm;
+    int present[kMaxShardsPerLayer];
+    int m = 0;
+    for (int i = 0; i < M; ++i)
+        if (shards[i].bitwidth != 0) present[m++] = i;
+
+    GemmBlocks bq, bo, b1, b2;
+    memset(&bq, 0, sizeof(bq)); memset(&bo, 0, sizeof(bo));
+    memset(&b1, 0, sizeof(b1)); memset(&b2, 0, sizeof(b2));
+    const bool f32 = (prec == STI_PREC_F32);
+    if (f32 && m > 0) {
+        InlineShardTable t;
+        memset(&t, 0, sizeof(t));
+        for (int p = 0; p < m; ++p) {
+            const sti_shard &s = shards[present[p]];
+            t.d[p] = ShardDesc{s.data, s.codebook, s.bitwidth, present[p]};
+        }
+        STI_TRY(launch_decode(nullptr, &t, m, wsh, ws + wl.w32, STI_F32, stream));
+    }
+    for (int p = 0; p < m; ++p) {
+        const sti_shard &s = shards[present[p]];
+        if (f32) {
+            const float *w = (const float *)(ws + wl.w32) + (size_t)p * wsh;
+            bq.b[p] = GemmBlock{w, nullptr, 32, present[p]};
+            bo.b[p] = GemmBlock{w + off_o, nullptr, 32, present[p]};
+            b1.b[p] = GemmBlock{w + off_1, nullptr, 32, present[p]};
+            b2.b[p] = GemmBlock{w + off_2, nullptr, 32, present[p]};
+        } else {
+            bq.b[p] = GemmBlock{block_start(s, 0), s.codebook, s.bitwidth, present[p]};
+            bo.b[p] = GemmBlock{block_start(s, off_o), s.codebook, s.bitwidth, present[p]};
+            b1.b[p] = GemmBlock{block_start(s, off_1), s.codebook, s.bitwidth, present[p]};
+            b2.b[p] = GemmBlock{block_start(s, off_2), s.codebook, s.bitwidth, present[p]};
+        }
+    }
+    void *qkv = ws + wl.qkv, *ctx = ws + wl.ctx, *h = ws + wl.h, *u = ws + wl.u;
+    float *pre = (float *)(ws + wl.pre);
+    const sti_dtype act_dtype = f32 ? STI_F32 : STI_F16;
+    auto gemm = [&](const GemmProblem &p, const GemmBlocks &blk) {
+        return f32 ? launch_gemm_f32(p, blk, stream) : launch_gemm_mfma(p, blk, stream);
+    };
+
+    GemmProblem p;
+    if (m > 0) {
+        memset(&p, 0, sizeof(p));
+        p.kind = GEMM_QKV; p.T = T; p.n_blocks = m; p.block_rows = 3 * dh; p.block_cols = dm;
+        p.d_head = dh; p.A = in; p.lda = dm; p.C = qkv; p.ldc = m * 3 * dh;
+        p.bias0 = prm.bq; p.bias1 = prm.bk; p.bias2 = prm.bv;
+        STI_TRY(gemm(p, bq));
+        if (f32) STI_TRY(launch_attention_f32((const float *)qkv, (float *)ctx, B, Lseq, m, dh, stream));
+        else STI_TRY(launch_attention_mfma(qkv, ctx, B, Lseq, m, dh, stream));
+    }
+    memset(&p, 0, sizeof(p));
+    p.kind = GEMM_OUT; p.T = T; p.n_blocks = m; p.block_rows = dm; p.block_cols = dh; p.d_head = dh;
+    p.A = ctx; p.lda = m * dh; p.C = pre; p.ldc = dm; p.bias0 = prm.bo; p.resid = in; p.ldr = dm;
+    STI_TRY(gemm(p, bo));
+    STI_TRY(launch_layernorm(pre, h, act_dtype, prm.ln1_g, prm.ln1_b, T, dm, d.ln_eps, stream));
+    if (m > 0) {
+        memset(&p, 0, sizeof(p));
+        p.kind = GEMM_FFN_UP; p.T = T; p.n_blocks = m; p.block_rows = f; p.block_cols = dm;
+        p.d_head = dh; p.A = h; p.lda = dm; p.C = u; p.ldc = m * f; p.bias0 = prm.b1;
+        STI_TRY(gemm(p, b1));
+    }
+    memset(&p, 0, sizeof(p));
+    p.kind = GEMM_FFN_DOWN; p.T = T; p.n_blocks = m; p.block_rows = dm; p.block_cols = f;
+    p.d_head = dh; p.A = u; p.lda = m * f; p.C = pre; p.ldc = dm; p.bias0 = prm.b2; p.resid = h;
+    p.ldr = dm;
+    STI_TRY(gemm(p, b2));
+    STI_TRY(launch_layernorm(pre, out, out_dtype, prm.ln2_g, prm.ln2_b, T, dm, d.ln_eps, stream));
+    return STI_OK;
+}
+
+sti_status check_io(const void *x, void *y, sti_dtype io, int64_t T, int d)
+{
+    if (io != STI_F32 && io != STI_F16 && io != STI_BF16) return STI_ERR_DTYPE;
+    if (T == 0) return STI_OK;
+    if (!x || !y) return STI_ERR_NULL;
+    if (!aligned(x, 16) || !aligned(y, 16)) return STI_ERR_ALIGN;
+    const size_t bytes = (size_t)T * d * (io == STI_F32 ? 4 : 2);
+    const uintptr_t a = (uintptr_t)x, b = (uintptr_t)y;
+    if (a < b + bytes && b < a + bytes) return STI_ERR_DIMS;  // x and y overlap
+    return STI_OK;
+}
+
 }  // namespace
 }  // namespace sti
 
@@ -156,6 +336,122 @@ sti_status sti_decode_shards(const sti_shard *shards, int n_shards, uint64_t wei
         e = launch_decode(nullptr, &t, n_shards, weights_per_shard, out, out_dtype, stream);
     }
     return e == hipSuccess ? STI_OK : STI_ERR_HIP;
+}
+
+}  // extern "C"
+
+extern "C" {
+
+size_t sti_workspace_bytes(const sti_dims *dims, int batch, int seq, sti_precision precision)
+{
+    if (check_dims(dims, batch, seq, precision) != STI_OK) return 0;
+    size_t t = workspace_layout(*dims, (int64_t)batch * seq, precision).total;
+    return t ? t : 256;
+}
+
+sti_status sti_layer_forward(const sti_dims *dims, const sti_shard *shards,
+                             const sti_layer_params *params, const void *x, void *y,
+                             sti_dtype io_dtype, int batch, int seq, sti_precision precision,
+                             void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    sti_status st = check_dims(dims, batch, seq, precision);
+    if (st != STI_OK) return st;
+    if (!shards) return STI_ERR_NULL;
+    st = check_params(params);
+    if (st != STI_OK) return st;
+    const int64_t T = (int64_t)batch * seq;
+    st = check_io(x, y, io_dtype, T, dims->d_model);
+    if (st != STI_OK) return st;
+    for (int i = 0; i < dims->n_heads; ++i) {
+        st = check_layer_shard(shards[i]);
+        if (st != STI_OK) return st;
+    }
+    const WorkspaceLayout wl = workspace_layout(*dims, T, precision);
+    if (!workspace || workspace_bytes < wl.total) return STI_ERR_WORKSPACE;
+    if (!aligned(workspace, 256)) return STI_ERR_ALIGN;
+    if (T == 0) return STI_OK;
+
+    hipStream_t stream = (hipStream_t)hip_stream;
+    uint8_t *ws = (uint8_t *)workspace;
+    const sti_dtype act = (precision == STI_PREC_F32) ? STI_F32 : STI_F16;
+    const void *in = x;
+    if (io_dtype != act) {
+        STI_TRY(launch_convert(x, io_dtype, ws + wl.act[0], act, (uint64_t)T * dims->d_model, stream));
+        in = ws + wl.act[0];
+    }
+    return run_layer(*dims, shards, *params, in, y, io_dtype, batch, seq, precision, ws, wl, stream);
+}
+
+sti_status sti_model_forward(const sti_dims *dims, int n_layers, const sti_shard *store,
+                             const sti_layer_params *params, const int8_t *plan, const void *x,
+                             void *y, sti_dtype io_dtype, int batch, int seq,
+                             sti_precision precision, void *workspace, size_t workspace_bytes,
+                             void *hip_stream)
+{
+    sti_status st = check_dims(dims, batch, seq, precision);
+    if (st != STI_OK) return st;
+    if (n_layers < 0) return STI_ERR_DIMS;
+    const int64_t T = (int64_t)batch * seq;
+    st = check_io(x, y, io_dtype, T, dims->d_model);
+    if (st != STI_OK) return st;
+    const int M = dims->n_heads;
+    if (n_layers > 0 && (!store || !params || !plan)) return STI_ERR_NULL;
+    std::vector<sti_shard> chosen;
+    try {
+        chosen.resize((size_t)n_layers * M);
+    } catch (const std::bad_alloc &) {
+        return STI_ERR_HIP;
+    }
+    for (int l = 0; l < n_layers; ++l) {
+        st = check_params(&params[l]);
+        if (st != STI_OK) return st;
+        for (int i = 0; i < M; ++i) {
+            const int k = plan[(size_t)l * M + i];
+            sti_shard &c = chosen[(size_t)l * M + i];
+            memset(&c, 0, sizeof(c));
+            if (k == 0) continue;
+            int slot;
+            if (valid_packed_bits(k)) slot = k - 2;
+            else if (k == 32) slot = 5;
+            else return STI_ERR_BITWIDTH;
+            const sti_shard &v = store[((size_t)l * M + i) * 6 + slot];
+            if (!v.data) return STI_ERR_MISSING_SHARD;
+            if (v.bitwidth != k) return STI_ERR_BITWIDTH;
+            st = check_decode_shard(v);
+            if (st != STI_OK) return st;
+            c = v;
+        }
+    }
+    const WorkspaceLayout wl = workspace_layout(*dims, T, precision);
+    if (!workspace || workspace_bytes < wl.total) return STI_ERR_WORKSPACE;
+    if (!aligned(workspace, 256)) return STI_ERR_ALIGN;
+    if (T == 0) return STI_OK;
+
+    hipStream_t stream = (hipStream_t)hip_stream;
+    uint8_t *ws = (uint8_t *)workspace;
+    const size_t io_bytes = (size_t)T * dims->d_model * (io_dtype == STI_F32 ? 4 : 2);
+    if (n_layers == 0) {
+        STI_TRY(hipMemcpyAsync(y, x, io_bytes, hipMemcpyDeviceToDevice, stream));
+        return STI_OK;
+    }
+    const sti_dtype act = (precision == STI_PREC_F32) ? STI_F32 : STI_F16;
+    const void *cur = x;
+    int next_buf = 0;
+    if (io_dtype != act) {
+        STI_TRY(launch_convert(x, io_dtype, ws + wl.act[0], act, (uint64_t)T * dims->d_model, stream));
+        cur = ws + wl.act[0];
+        next_buf = 1;
+    }
+    for (int l = 0; l < n_layers; ++l) {
+        const bool last = (l == n_layers - 1);
+        void *out = last ? y : (void *)(ws + wl.act[next_buf]);
+        st = run_layer(*dims, &chosen[(size_t)l * M], params[l], cur, out, last ? io_dtype : act,
+                       batch, seq, precision, ws, wl, stream);
+        if (st != STI_OK) return st;
+        cur = out;
+        next_buf ^= 1;
+    }
+    return STI_OK;
 }
 
 }  // extern "C"

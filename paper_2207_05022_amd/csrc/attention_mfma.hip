@@ -1,0 +1,169 @@
+// Per-head attention on the matrix cores: C = softmax(Q K^T / sqrt(dh)) V for
+// one (sequence, present head) per workgroup column (Section "A primer on
+// transformer": each head contributes its own attention score).
+//
+// Everything is computed transposed so that the softmax never crosses lanes:
+//   S^T = K Q^T   -> a lane owns one query (MFMA column) and 16 keys per
+//                    32-key block in its accumulator registers;
+//   O^T = V^T P^T -> the probabilities are already in the register layout the
+//                    B operand needs once the key order inside each k16 step
+//                    is permuted, and V^T is read from LDS in that same order.
+// The running max / sum (online softmax) is per lane; lanes l and l^32 own the
+// two halves of a query's keys and exchange their maxima once per key block.
+#include "sti_internal.hpp"
+
+namespace sti {
+namespace {
+
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef _Float16 half4 __attribute__((ext_vector_type(4)));
+typedef float float16v __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int DH = 64;
+constexpr int KPAD = DH + 8;   // padded K row (halves)
+constexpr int QB = 128;        // queries per workgroup (4 waves x 32)
+
+__device__ inline int vt_stride(int Lp) { return Lp + 8; }
+
+__global__ __launch_bounds__(256) void attention_mfma_kernel(const _Float16 *qkv, _Float16 *ctx,
+                                                             int L, int Lp, int m)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+    _Float16 *Ks = (_Float16 *)smem_raw;                 // [Lp][KPAD]
+    _Float16 *Vt = Ks + (size_t)Lp * KPAD;               // [DH][Lp + 8]
+    const int vts = vt_stride(Lp);
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int g = lane >> 5, lr = lane & 31;
+    const int b = blockIdx.z, p = blockIdx.y;
+    const int64_t ld = (int64_t)m * 3 * DH;
+    const _Float16 *base = qkv + (int64_t)b * L * ld + (int64_t)p * 3 * DH;
+
+    // stage K (row-major) and V (transposed) of this head; rows >= L are zero
+    for (int r = tid >> 3; r < Lp; r += 32) {
+        const int c = (tid & 7) * 8;
+        u32x4 kv = {0, 0, 0, 0}, vv = {0, 0, 0, 0};
+        if (r < L) {
+            kv = *(const u32x4 *)(base + (int64_t)r * ld + DH + c);
+            vv = *(const u32x4 *)(base + (int64_t)r * ld + 2 * DH + c);
+        }
+        *(u32x4 *)(Ks + (size_t)r * KPAD + c) = kv;
+        const _Float16 *vh = (const _Float16 *)&vv;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) Vt[(size_t)(c + i) * vts + r] = vh[i];
+    }
+
+    // this lane's query row as the B operand of S^T = K Q^T
+    const int q = blockIdx.x * QB + wave * 32 + lr;
+    half8 qf[4];
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+        u32x4 v = {0, 0, 0, 0};
+        if (q < L) v = *(const u32x4 *)(base + (int64_t)q * ld + s * 16 + g * 8);
+        qf[s] = __builtin_bit_cast(half8, v);
+    }
+    __syncthreads();
+
+    const float scale = 0.125f * 1.44269504088896340736f;   // 1/sqrt(64) * log2(e)
+    float run_max = -INFINITY, run_sum = 0.f;
+    float16v o[2];
+#pragma unroll
+    for (int e = 0; e < 2; ++e)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) o[e][v] = 0.f;
+
+    const int nkb = Lp / 32;
+    for (int kb = 0; kb < nkb; ++kb) {
+        float16v s_acc;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) s_acc[v] = 0.f;
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            half8 kf = *(const half8 *)(Ks + (size_t)(kb * 32 + lr) * KPAD + s * 16 + g * 8);
+            s_acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf, qf[s], s_acc, 0, 0, 0);
+        }
+        // scores of keys kb*32 + (v/4)*8 + g*4 + v%4 for this lane's query
+        float bmax = -INFINITY;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int key = kb * 32 + (v >> 2) * 8 + g * 4 + (v & 3);
+            float x = s_acc[v] * scale;
+            x = (key < L) ? x : -INFINITY;
+            s_acc[v] = x;
+            bmax = fmaxf(bmax, x);
+        }
+        bmax = fmaxf(bmax, __shfl_xor(bmax, 32, 64));
+        const float new_max = fmaxf(run_max, bmax);
+        const float alpha = __builtin_amdgcn_exp2f(run_max - new_max);
+        run_max = new_max;
+        float psum = 0.f;
+        uint32_t pk[8];
+#pragma unroll
+        for (int v = 0; v < 16; v += 2) {
+            float p0 = __builtin_amdgcn_exp2f(s_acc[v] - new_max);
+            float p1 = __builtin_amdgcn_exp2f(s_acc[v + 1] - new_max);
+            psum += p0 + p1;
+            pk[v / 2] = (uint32_t)__builtin_bit_cast(uint16_t, (_Float16)p0) |
+                        ((uint32_t)__builtin_bit_cast(uint16_t, (_Float16)p1) << 16);
+        }
+        run_sum = run_sum * alpha + psum;
+#pragma unroll
+        for (int e = 0; e < 2; ++e)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) o[e][v] *= alpha;
+        // O^T += V^T P^T over the two k16 steps of this key block
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2) {
+            u32x4 pv = {pk[4 * s2], pk[4 * s2 + 1], pk[4 * s2 + 2], pk[4 * s2 + 3]};
+            half8 pf = __builtin_bit_cast(half8, pv);
+            const int key0 = kb * 32 + (2 * s2) * 8 + g * 4;
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {
+                const _Float16 *vrow = Vt + (size_t)(e * 32 + lr) * vts + key0;
+                u32x2 lo = *(const u32x2 *)vrow;
+                u32x2 hi = *(const u32x2 *)(vrow + 8);
+                u32x4 vv = {lo.x, lo.y, hi.x, hi.y};
+                o[e] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8, vv), pf,
+                                                              o[e], 0, 0, 0);
+            }
+        }
+    }
+    run_sum += __shfl_xor(run_sum, 32, 64);
+    if (q >= L) return;
+    const float inv = 1.0f / run_sum;
+    _Float16 *out = ctx + ((int64_t)b * L + q) * ((int64_t)m * DH) + (int64_t)p * DH;
+#pragma unroll
+    for (int e = 0; e < 2; ++e)
+#pragma unroll
+        for (int v4 = 0; v4 < 4; ++v4) {
+            half4 h;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) h[i] = (_Float16)(o[e][v4 * 4 + i] * inv);
+            *(half4 *)(out + e * 32 + v4 * 8 + g * 4) = h;
+        }
+}
+
+}  // namespace
+
+hipError_t launch_attention_mfma(const void *qkv, void *ctx, int B, int L, int m, int dh,
+                                 hipStream_t stream)
+{
+    if (B <= 0 || L <= 0 || m <= 0) return hipSuccess;
+    if (dh != DH) return hipErrorInvalidValue;
+    const int Lp = (L + 31) / 32 * 32;
+    const size_t lds = ((size_t)Lp * KPAD + (size_t)DH * (Lp + 8)) * sizeof(_Float16);
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void *)attention_mfma_kernel,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    dim3 grid((L + QB - 1) / QB, m, B);
+    attention_mfma_kernel<<<grid, dim3(256), lds, stream>>>((const _Float16 *)qkv, (_Float16 *)ctx,
+                                                           L, Lp, m);
+    return hipGetLastError();
+}
+
+}  // namespace sti

@@ -1,0 +1,132 @@
+// Row-wise and elementwise helpers of the layer: LayerNorm over d features
+// (biased variance, Section "A primer on transformer" runs stock BERT layers)
+// and activation type conversion.
+#include "sti_internal.hpp"
+
+namespace sti {
+namespace {
+
+__device__ inline float wave_sum(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+__device__ inline uint16_t f32_to_bf16_bits(float v)
+{
+    uint32_t u = __builtin_bit_cast(uint32_t, v);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x0040u);
+    return (uint16_t)((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);
+}
+__device__ inline float bf16_bits_to_f32(uint16_t b)
+{
+    return __builtin_bit_cast(float, (uint32_t)b << 16);
+}
+
+template <int DT> struct Elem;
+template <> struct Elem<STI_F32> {
+    typedef float type;
+    static __device__ inline float load(const float *p) { return *p; }
+    static __device__ inline void store(float *p, float v) { *p = v; }
+};
+template <> struct Elem<STI_F16> {
+    typedef _Float16 type;
+    static __device__ inline float load(const _Float16 *p) { return (float)*p; }
+    static __device__ inline void store(_Float16 *p, float v) { *p = (_Float16)v; }
+};
+template <> struct Elem<STI_BF16> {
+    typedef uint16_t type;
+    static __device__ inline float load(const uint16_t *p) { return bf16_bits_to_f32(*p); }
+    static __device__ inline void store(uint16_t *p, float v) { *p = f32_to_bf16_bits(v); }
+};
+
+// One wave per row; two-pass mean / variance in float32.
+template <int DT>
+__global__ __launch_bounds__(256) void layernorm_kernel(const float *pre, typename Elem<DT>::type *y,
+                                                        const float *g, const float *b, int T, int d,
+                                                        float eps)
+{
+    const int row = blockIdx.x * 4 + threadIdx.x / 64;
+    const int lane = threadIdx.x % 64;
+    if (row >= T) return;
+    const float *r = pre + (int64_t)row * d;
+    float s = 0.f;
+    for (int c = lane; c < d; c += 64) s += r[c];
+    const float mean = wave_sum(s) / (float)d;
+    float q = 0.f;
+    for (int c = lane; c < d; c += 64) {
+        float t = r[c] - mean;
+        q = fmaf(t, t, q);
+    }
+    const float var = wave_sum(q) / (float)d;
+    const float inv = 1.0f / sqrtf(var + eps);
+    typename Elem<DT>::type *o = y + (int64_t)row * d;
+    for (int c = lane; c < d; c += 64) Elem<DT>::store(o + c, (r[c] - mean) * inv * g[c] + b[c]);
+}
+
+template <int SRC, int DST>
+__global__ __launch_bounds__(256) void convert_kernel(const typename Elem<SRC>::type *src,
+                                                      typename Elem<DST>::type *dst, uint64_t n)
+{
+    uint64_t i = (uint64_t)blockIdx.x * 256 + threadIdx.x;
+    const uint64_t stride = (uint64_t)gridDim.x * 256;
+    for (; i < n; i += stride) Elem<DST>::store(dst + i, Elem<SRC>::load(src + i));
+}
+
+template <int SRC>
+hipError_t convert_from(const void *src, void *dst, sti_dtype dst_dtype, uint64_t n, dim3 grid,
+                        hipStream_t stream)
+{
+    typedef typename Elem<SRC>::type S;
+    switch (dst_dtype) {
+        case STI_F32:
+            convert_kernel<SRC, STI_F32><<<grid, 256, 0, stream>>>((const S *)src, (float *)dst, n);
+            break;
+        case STI_F16:
+            convert_kernel<SRC, STI_F16><<<grid, 256, 0, stream>>>((const S *)src, (_Float16 *)dst, n);
+            break;
+        case STI_BF16:
+            convert_kernel<SRC, STI_BF16><<<grid, 256, 0, stream>>>((const S *)src, (uint16_t *)dst, n);
+            break;
+    }
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_layernorm(const float *pre, void *y, sti_dtype out_dtype, const float *g,
+                            const float *b, int T, int d, float eps, hipStream_t stream)
+{
+    if (T <= 0 || d <= 0) return hipSuccess;
+    dim3 grid((T + 3) / 4);
+    switch (out_dtype) {
+        case STI_F32:
+            layernorm_kernel<STI_F32><<<grid, 256, 0, stream>>>(pre, (float *)y, g, b, T, d, eps);
+            break;
+        case STI_F16:
+            layernorm_kernel<STI_F16><<<grid, 256, 0, stream>>>(pre, (_Float16 *)y, g, b, T, d, eps);
+            break;
+        case STI_BF16:
+            layernorm_kernel<STI_BF16><<<grid, 256, 0, stream>>>(pre, (uint16_t *)y, g, b, T, d, eps);
+            break;
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_convert(const void *src, sti_dtype src_dtype, void *dst, sti_dtype dst_dtype,
+                          uint64_t n, hipStream_t stream)
+{
+    if (n == 0) return hipSuccess;
+    uint64_t blocks = (n + 255) / 256;
+    if (blocks > 65536) blocks = 65536;
+    dim3 grid((uint32_t)blocks);
+    switch (src_dtype) {
+        case STI_F32: return convert_from<STI_F32>(src, dst, dst_dtype, n, grid, stream);
+        case STI_F16: return convert_from<STI_F16>(src, dst, dst_dtype, n, grid, stream);
+        case STI_BF16: return convert_from<STI_BF16>(src, dst, dst_dtype, n, grid, stream);
+    }
+    return hipErrorInvalidValue;
+}
+
+}  // namespace sti

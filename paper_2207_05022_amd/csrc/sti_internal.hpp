@@ -14,7 +14,7 @@ struct ShardDesc {
     const void *data;       // packed stream or float32 values
     const float *codebook;  // 2^bits centroids (unused for 32)
     int32_t bits;           // 2..6 or 32
-    int32_t tag;            // caller-defined (original shard id in layer kernels)
+    int32_t tag;            // original shard id inside its layer
 };
 
 struct InlineShardTable {
@@ -27,29 +27,62 @@ struct InlineShardTable {
 hipError_t launch_decode(const ShardDesc *table, const InlineShardTable *inline_table, int n_shards,
                          uint64_t n, void *out, sti_dtype out_dtype, hipStream_t stream);
 
-// ---- reference-precision (float32) layer kernels: layer_f32.hip -------------
+// ---- layer kernels ----------------------------------------------------------
+// The four projections of a layer over its present shards, seen as GEMMs
+// C[T x N] = A[T x K] * W^T whose weight operand is cut into per-shard blocks:
+enum GemmKind : int32_t {
+    GEMM_QKV = 0,       // blocks along N: block p = [3*dh x d] (Wq,Wk,Wv of shard p); + bq|bk|bv
+    GEMM_FFN_UP = 1,    // blocks along N: block p = [f x d];   + b1 slice, then GELU
+    GEMM_OUT = 2,       // blocks along K: block p = [d x dh];  + bo[n] + residual
+    GEMM_FFN_DOWN = 3   // blocks along K: block p = [d x f];   + b2[n] + residual
+};
+
 struct GemmBlock {
-    const void *w;          // weights of this block (float32 for the f32 path; stream/float32 for mfma)
-    const float *codebook;  // mfma path only
-    int32_t bits;           // mfma path only
-    int32_t shard;          // original shard id (selects bias slices)
+    const void *w;          // start of the block's weights: float32 values, or a k-bit stream
+    const float *codebook;  // centroids when bits <= 6
+    int32_t bits;           // 2..6, 32
+    int32_t shard;          // original shard id (selects the bias slice)
 };
 
 struct GemmBlocks {
     GemmBlock b[kMaxShardsPerLayer];
 };
 
-enum GemmKind : int32_t {
-    GEMM_QKV = 0,      // N-split: block p holds [3*dh x d]; bias from bq/bk/bv of shard
-    GEMM_FFN_UP = 1,   // N-split: block p holds [f x d]; bias b1 of shard; GELU
-    GEMM_OUT = 2,      // K-split: block p holds [d x dh]; + bias[n] + residual
-    GEMM_FFN_DOWN = 3  // K-split: block p holds [d x f];  + bias[n] + residual
+struct GemmProblem {
+    GemmKind kind;
+    int32_t T;          // rows of A and C
+    int32_t n_blocks;   // present shards
+    int32_t block_rows; // N-split: rows per block; K-split: N (= d)
+    int32_t block_cols; // N-split: K (= d);        K-split: columns per block
+    int32_t d_head;     // QKV bias selection
+    const void *A;      // [T x K], row stride lda elements
+    int32_t lda;
+    void *C;            // [T x N], row stride ldc elements
+    int32_t ldc;
+    const float *bias0, *bias1, *bias2;  // QKV: bq,bk,bv; FFN_UP: b1; OUT/FFN_DOWN: bias[N]
+    const void *resid;  // OUT/FFN_DOWN: [T x N] residual, row stride ldr
+    int32_t ldr;
 };
 
-struct LayerGeom {
-    int32_t d, M, dh, f, m;   // m = number of present shards
-    int32_t B, L, T;
-    float eps;
-};
+// float32 path (layer_f32.hip): A, C, resid are float32; weights are float32 blocks.
+hipError_t launch_gemm_f32(const GemmProblem &p, const GemmBlocks &blocks, hipStream_t stream);
+// qkv [T x m*3*dh] float32 (per shard: q, k, v each dh wide) -> ctx [T x m*dh] float32
+hipError_t launch_attention_f32(const float *qkv, float *ctx, int B, int L, int m, int dh,
+                                hipStream_t stream);
+
+// binary16 MFMA path (gemm_mfma.hip, attention_mfma.hip): A is binary16; C is
+// binary16 for QKV / FFN_UP and float32 (pre-LayerNorm) for OUT / FFN_DOWN;
+// resid is binary16; weights are decoded inside the loader.
+hipError_t launch_gemm_mfma(const GemmProblem &p, const GemmBlocks &blocks, hipStream_t stream);
+hipError_t launch_attention_mfma(const void *qkv, void *ctx, int B, int L, int m, int dh,
+                                 hipStream_t stream);
+
+// rowops.hip
+// y[t][:] = LayerNorm(pre[t][:]) * g + b; pre float32 [T x d]; y of out_dtype.
+hipError_t launch_layernorm(const float *pre, void *y, sti_dtype out_dtype, const float *g,
+                            const float *b, int T, int d, float eps, hipStream_t stream);
+// elementwise conversion between activation types
+hipError_t launch_convert(const void *src, sti_dtype src_dtype, void *dst, sti_dtype dst_dtype,
+                          uint64_t n, hipStream_t stream);
 
 }  // namespace sti

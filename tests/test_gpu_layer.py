@@ -1,0 +1,217 @@
+"""GPU parity: sti_layer_forward / sti_model_forward (through the C ABI) against the
+CPU oracle.
+
+Tolerance (derivation in the design doc): max |y_gpu - y_ref| / max |y_ref| <= 1e-5 for the
+float32 path and <= 2e-2 for the binary16 matrix-core path.
+"""
+import json
+import math
+import os
+
+import numpy as np
+import pytest
+
+import sti_synth as S
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-5, "mfma": 2e-2}
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+SMALL = S.Dims(48, 3, 16, 32, 1e-12)
+MID = S.Dims(128, 4, 64, 64, 1e-12)
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    import paper_2207_05022_amd as P
+    from paper_2207_05022_amd import device as D
+    assert torch.cuda.is_available(), "needs a GPU"
+    return torch, P, D
+
+
+def rel_err(got, want):
+    return float(np.max(np.abs(got.astype(np.float64) - want)) / max(np.max(np.abs(want)), 1e-30))
+
+
+def run_gpu(gpu, wl, prec, model=True, x=None):
+    torch, P, D = gpu
+    precision = P.STI_PREC_F32 if prec == "f32" else P.STI_PREC_F16_MFMA
+    shards, params, xd = D.upload_workload(wl)
+    if x is not None:
+        xd = torch.from_numpy(np.ascontiguousarray(x)).cuda()
+    y = torch.full_like(xd, float("nan"))
+    B, L = int(xd.shape[0]), int(xd.shape[1])
+    nbytes = P.sti_workspace_bytes(wl.dims, B, L, precision)
+    assert nbytes > 0
+    ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    if model:
+        P.sti_model_forward(wl.dims, D.store_from_plan(shards), params, wl.plan, xd, y, precision, ws)
+    else:
+        assert wl.n_layers == 1
+        P.sti_layer_forward(wl.dims, shards[0], params[0], xd, y, precision, ws)
+    torch.cuda.synchronize()
+    return y.float().cpu().numpy()
+
+
+# ------------------------------------------------------------------ float32 path
+
+def test_f32_tiny_hand_derived_layer(gpu):
+    """The hand-derived fixture, straight against its printed expectations."""
+    fx = json.load(open(os.path.join(GOLDEN, "tiny_layer.json")))
+    dims = S.Dims(**fx["dims"])
+    s = math.sqrt(math.sqrt(2.0) * math.log(3.0))
+    mat = lambda m: np.array([[s if v == "s" else v for v in row] for row in m], dtype=np.float32)
+    shards = []
+    for name in ("shard0", "shard1"):
+        b = fx[name]
+        flat = np.concatenate([mat(b[k]).ravel() for k in ("Wq", "Wk", "Wv", "Wo", "W1", "W2")])
+        shards.append(S.Shard(32, flat, None))
+    params = S.LayerParams(**{k: np.array(v, dtype=np.float32) for k, v in fx["params"].items()})
+    wl = S.Workload("tiny", dims, 1, 2, np.array([[32, 32]], dtype=np.int8), [shards], [params],
+                    np.array(fx["x"], dtype=np.float32))
+    y = run_gpu(gpu, wl, "f32", model=False)
+    assert rel_err(y, np.array(fx["expected"]["y"])) <= 1e-5
+
+
+@pytest.mark.parametrize("B,L", [(1, 1), (2, 7), (3, 70), (1, 130)])
+def test_f32_small_mixed_layer(gpu, oracle_mod, B, L):
+    wl = S.small_workload(100 + L, SMALL, 1, B, L, plan=np.array([[3, 32, 6]]))
+    want = oracle_mod.layer_forward(SMALL, wl.shards[0], wl.params[0], wl.x)
+    got = run_gpu(gpu, wl, "f32", model=False)
+    assert rel_err(got, want) <= TOL["f32"]
+
+
+@pytest.mark.parametrize("plan", [[0, 0, 0], [0, 5, 0], [2, 0, 4]])
+def test_f32_absent_shards(gpu, oracle_mod, plan):
+    wl = S.small_workload(7, SMALL, 1, 2, 9, plan=np.array([plan]))
+    want = oracle_mod.layer_forward(SMALL, wl.shards[0], wl.params[0], wl.x)
+    got = run_gpu(gpu, wl, "f32", model=False)
+    assert rel_err(got, want) <= TOL["f32"]
+
+
+@pytest.mark.parametrize("io", ["f32", "f16"])
+def test_f32_small_model_all_bitwidths(gpu, oracle_mod, io):
+    wl = S.small_workload(9, MID, 3, 2, 33, n_absent=1, io_dtype=io)
+    want = oracle_mod.model_forward(MID, wl.shards, wl.params, wl.x)
+    got = run_gpu(gpu, wl, "f32")
+    tol = TOL["f32"] if io == "f32" else 1e-3  # output rounded to binary16
+    assert rel_err(got, want) <= tol
+
+
+def test_f32_bf16_io(gpu, oracle_mod):
+    torch, P, D = gpu
+    wl = S.small_workload(10, MID, 2, 1, 17)
+    xb = torch.from_numpy(wl.x).to(torch.bfloat16)
+    wl.x = xb.float().numpy()
+    want = oracle_mod.model_forward(MID, wl.shards, wl.params, wl.x)
+    shards, params, _ = D.upload_workload(wl)
+    xd = xb.cuda(); y = torch.empty_like(xd)
+    ws = torch.empty(P.sti_workspace_bytes(MID, 1, 17, P.STI_PREC_F32), dtype=torch.uint8, device="cuda")
+    P.sti_model_forward(MID, D.store_from_plan(shards), params, wl.plan, xd, y, P.STI_PREC_F32, ws)
+    torch.cuda.synchronize()
+    assert rel_err(y.float().cpu().numpy(), want) <= 8e-3  # output rounded to bfloat16
+
+
+def test_f32_config0(gpu, oracle_mod):
+    wl = S.config0()
+    want = oracle_mod.layer_forward(wl.dims, wl.shards[0], wl.params[0], wl.x)
+    got = run_gpu(gpu, wl, "f32", model=False)
+    assert rel_err(got, want) <= TOL["f32"]
+
+
+def test_f32_config2(gpu, oracle_mod):
+    wl = S.config2()
+    want = oracle_mod.model_forward(wl.dims, wl.shards, wl.params, wl.x)
+    got = run_gpu(gpu, wl, "f32")
+    assert rel_err(got, want) <= TOL["f32"]
+
+
+def test_f32_config3(gpu, oracle_mod):
+    wl = S.config3()
+    want = oracle_mod.model_forward(wl.dims, wl.shards, wl.params, wl.x)
+    got = run_gpu(gpu, wl, "f32")
+    assert rel_err(got, want) <= TOL["f32"]
+
+
+def test_empty_batch_and_zero_layers(gpu):
+    torch, P, D = gpu
+    wl = S.small_workload(3, SMALL, 1, 1, 4)
+    shards, params, xd = D.upload_workload(wl)
+    ws = torch.empty(max(256, P.sti_workspace_bytes(SMALL, 1, 4, 0)), dtype=torch.uint8, device="cuda")
+    y = torch.zeros_like(xd)
+    P.sti_model_forward(SMALL, D.store_from_plan([]), [], np.zeros((0, 3), np.int8), xd, y, 0, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(xd, y)
+    x0 = xd[:0].contiguous(); y0 = torch.empty_like(x0)
+    P.sti_layer_forward(SMALL, shards[0], params[0], x0, y0, 0, ws)
+    torch.cuda.synchronize()
+
+
+# ------------------------------------------------------------------ binary16 matrix-core path
+
+@pytest.mark.parametrize("B,L", [(1, 1), (2, 33), (1, 128), (3, 100), (1, 300)])
+def test_mfma_small_mixed_layer(gpu, oracle_mod, B, L):
+    wl = S.small_workload(200 + L, MID, 1, B, L, plan=np.array([[3, 32, 6, 5]]))
+    want = oracle_mod.layer_forward(MID, wl.shards[0], wl.params[0], wl.x)
+    got = run_gpu(gpu, wl, "mfma", model=False)
+    assert rel_err(got, want) <= TOL["mfma"]
+
+
+@pytest.mark.parametrize("plan", [[0, 0, 0, 0], [0, 4, 0, 0], [2, 0, 32, 0]])
+def test_mfma_absent_shards(gpu, oracle_mod, plan):
+    wl = S.small_workload(17, MID, 1, 2, 40, plan=np.array([plan]))
+    want = oracle_mod.layer_forward(MID, wl.shards[0], wl.params[0], wl.x)
+    got = run_gpu(gpu, wl, "mfma", model=False)
+    assert rel_err(got, want) <= TOL["mfma"]
+
+
+@pytest.mark.parametrize("io", ["f32", "f16"])
+def test_mfma_small_model(gpu, oracle_mod, io):
+    wl = S.small_workload(19, MID, 4, 2, 65, n_absent=1, io_dtype=io)
+    want = oracle_mod.model_forward(MID, wl.shards, wl.params, wl.x)
+    got = run_gpu(gpu, wl, "mfma")
+    assert rel_err(got, want) <= TOL["mfma"]
+
+
+def test_mfma_config0(gpu, oracle_mod):
+    wl = S.config0()
+    want = oracle_mod.layer_forward(wl.dims, wl.shards[0], wl.params[0], wl.x)
+    got = run_gpu(gpu, wl, "mfma", model=False)
+    assert rel_err(got, want) <= TOL["mfma"]
+
+
+def test_mfma_config2(gpu, oracle_mod):
+    wl = S.config2()
+    want = oracle_mod.model_forward(wl.dims, wl.shards, wl.params, wl.x)
+    got = run_gpu(gpu, wl, "mfma")
+    assert rel_err(got, want) <= TOL["mfma"]
+
+
+def test_mfma_config3(gpu, oracle_mod):
+    wl = S.config3()
+    want = oracle_mod.model_forward(wl.dims, wl.shards, wl.params, wl.x)
+    got = run_gpu(gpu, wl, "mfma")
+    assert rel_err(got, want) <= TOL["mfma"]
+
+
+def test_mfma_config4_full_batch_sampled_sequences(gpu, oracle_mod):
+    """Full-size batched run; sequences are independent, so the oracle checks a sample."""
+    wl = S.config4()
+    got = run_gpu(gpu, wl, "mfma")
+    assert np.all(np.isfinite(got))
+    for b in (0, 13, 31):
+        want = oracle_mod.model_forward(wl.dims, wl.shards, wl.params, wl.x[b:b + 1])
+        assert rel_err(got[b:b + 1], want) <= TOL["mfma"], b
+
+
+def test_mfma_rejects_unsupported_dims(gpu):
+    torch, P, D = gpu
+    assert P.sti_workspace_bytes(SMALL, 1, 8, P.STI_PREC_F16_MFMA) == 0
+    wl = S.small_workload(3, SMALL, 1, 1, 8)
+    shards, params, xd = D.upload_workload(wl)
+    y = torch.empty_like(xd)
+    ws = torch.empty(1 << 20, dtype=torch.uint8, device="cuda")
+    with pytest.raises(P.StiError) as ei:
+        P.sti_layer_forward(SMALL, shards[0], params[0], xd, y, P.STI_PREC_F16_MFMA, ws)
+    assert ei.value.status == 2
