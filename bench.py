@@ -1,0 +1,202 @@
+#!/usr/bin/env python3
+"""Throughput of the shard-decode + encoder-layer path on one MI355X.
+
+One step = one pass of the whole path over one batch: a 12-layer mixed-bitwidth
+BERT-base forward (decode fused into the projections, attention, LayerNorms)
+over 32 x 128 tokens.  The same run also times the standalone shard-decode
+entry point on the 1 GiB packed stream and the CPU oracle on a bounded sample.
+Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+from types import SimpleNamespace
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+METRIC = "BERT layer fwd tokens/s (mixed-bit shards); shard decode GB/s vs HBM peak"
+HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
+MFMA_F16_PEAK_TFLOPS = 2500.0  # MI355X dense fp16 MFMA, published
+
+
+def layer_flops_per_token(dims, seq, present):
+    """Algorithmic flops per token of one layer with `present` shards (2 flops per multiply-add)."""
+    d, dh, f = dims.d_model, dims.d_head, dims.ffn_per_shard
+    proj = 2 * present * (4 * d * dh + 2 * d * f)
+    attn = 4 * seq * dh * present
+    return proj + attn
+
+
+def gemm_flops(dims, tokens, present, kind):
+    d, dh, f = dims.d_model, dims.d_head, dims.ffn_per_shard
+    per_shard = {"gemm_qkv": 3 * dh * d, "gemm_out": d * dh, "gemm_ffn_up": f * d, "gemm_ffn_down": d * f}
+    return 2.0 * tokens * present * per_shard[kind]
+
+
+def bench_model(P, D, torch, S, steps, warmup):
+    wl = S.config4()
+    dims = wl.dims
+    shards, params, x = D.upload_workload(wl)
+    store = P.binding.make_store(D.store_from_plan(shards))
+    y = torch.empty_like(x)
+    prec = P.STI_PREC_F16_MFMA
+    ws = torch.empty(P.sti_workspace_bytes(dims, wl.batch, wl.seq, prec), dtype=torch.uint8, device="cuda")
+
+    def step():
+        P.sti_model_forward(dims, store, params, wl.plan, x, y, prec, ws)
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall / steps * 1e3
+    tokens_per_s = wl.tokens * steps / wall
+
+    # second pass of the same steps with every launch bracketed by events on the launch stream
+    P.sti_profile_begin()
+    for _ in range(steps):
+        step()
+    prof = P.sti_profile_end()
+    gemm_kinds = ("gemm_qkv", "gemm_out", "gemm_ffn_up", "gemm_ffn_down")
+    present_total = int((wl.plan != 0).sum())
+    gemm_launches = sum(prof[k][0] for k in gemm_kinds)
+    gemm_ms = sum(prof[k][1] for k in gemm_kinds)
+    flops_per_forward_gemm = sum(gemm_flops(dims, wl.tokens, present_total, k) for k in gemm_kinds)
+    launches_per_forward = gemm_launches / steps
+    flops_per_launch = flops_per_forward_gemm / launches_per_forward
+    avg_launch_ms = gemm_ms / gemm_launches
+    achieved_tflops = flops_per_launch / (avg_launch_ms * 1e-3) / 1e12
+    total_flops = sum(layer_flops_per_token(dims, wl.seq, int((wl.plan[l] != 0).sum())) for l in range(wl.n_layers)) * wl.tokens
+    out = {
+        "workload": wl,
+        "tokens_per_s": tokens_per_s,
+        "ms_per_step": ms_per_step,
+        "whole_path_tflops": total_flops / (ms_per_step * 1e-3) / 1e12,
+        "roofline": {
+            "bound": "mfma", "kernel": "gemm_mfma_kernel (QKV, O, FFN1, FFN2 projections, fused decode)",
+            "achieved": round(achieved_tflops, 2), "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s",
+            "frac": round(achieved_tflops / MFMA_F16_PEAK_TFLOPS, 4), "traffic": None,
+            "avg_launch_us": round(avg_launch_ms * 1e3, 2), "launches_per_step": launches_per_forward,
+            "flops_per_launch": flops_per_launch,
+        },
+        "kernel_ms_per_step": {k: round(v[1] / steps, 4) for k, v in prof.items() if v[0]},
+    }
+    return out, (wl, y)
+
+
+def bench_decode(P, torch, S, steps, warmup):
+    ds = S.config1()
+    n = ds.weights_per_shard
+    packed = torch.from_numpy(ds.packed).cuda()
+    cb_host = np.zeros((ds.n_shards, 64), dtype=np.float32)
+    for s, c in enumerate(ds.codebooks):
+        cb_host[s, :c.size] = c
+    cbs = torch.from_numpy(cb_host).cuda()
+    shards = [SimpleNamespace(bitwidth=int(ds.bitwidths[s]), data=packed[int(ds.offsets[s]):], codebook=cbs[s])
+              for s in range(ds.n_shards)]
+    arr = P.binding._shard_array(shards)
+    out = torch.empty(ds.n_shards * n, dtype=torch.float16, device="cuda")
+    ws = torch.empty(max(16, P.sti_decode_workspace_bytes(ds.n_shards)), dtype=torch.uint8, device="cuda")
+    for _ in range(warmup):
+        P.sti_decode_shards(arr, n, out, ws)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        P.sti_decode_shards(arr, n, out, ws)
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) / steps * 1e3
+    P.sti_profile_begin()
+    for _ in range(steps):
+        P.sti_decode_shards(arr, n, out, ws)
+    prof = P.sti_profile_end()
+    kern_ms = prof["decode"][1] / prof["decode"][0]
+    algo_bytes = ds.packed.nbytes + out.numel() * 2 + sum(c.nbytes for c in ds.codebooks)
+    gbs = algo_bytes / (kern_ms * 1e-3) / 1e9
+    res = {
+        "workload": f"config1: {ds.n_shards} BERT-base shards, {ds.packed.nbytes} packed bytes split evenly over k=2..6, fp16 out",
+        "value": round(algo_bytes / (wall_ms * 1e-3) / 1e9, 1), "unit": "GB/s (packed in + fp16 out, whole call)",
+        "ms_per_call": round(wall_ms, 4),
+        "roofline": {"bound": "hbm", "kernel": "decode_kernel", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": None,
+                     "avg_launch_us": round(kern_ms * 1e3, 2), "bytes_per_launch": algo_bytes},
+    }
+    return res, ds
+
+
+def cpu_baselines(S, wl, ds):
+    """The oracle as it stands, on a bounded sample of both workloads."""
+    import oracle
+    threads = oracle.num_threads()
+    nseq = 2
+    t0 = time.perf_counter()
+    oracle.model_forward(wl.dims, wl.shards, wl.params, wl.x[:nseq])
+    dt = time.perf_counter() - t0
+    model = {"value": round(nseq * wl.seq / dt, 2), "unit": "tokens/s", "cores": threads, "kind": "oracle",
+             "sample": f"{nseq} of {wl.batch} sequences through all {wl.n_layers} layers ({dt:.1f} s)"}
+    # decode: a few shards of every bitwidth
+    pick = []
+    for k in (2, 3, 4, 5, 6):
+        idx = np.nonzero(ds.bitwidths == k)[0][:8]
+        pick += [ds.shard(int(i)) for i in idx]
+    t0 = time.perf_counter()
+    out = oracle.decode_shards(pick, ds.weights_per_shard, oracle.F16)
+    dt = time.perf_counter() - t0
+    nbytes = sum(s.data.nbytes for s in pick) + out.nbytes
+    dec = {"value": round(nbytes / dt / 1e9, 3), "unit": "GB/s", "cores": threads, "kind": "oracle",
+           "sample": f"{len(pick)} of {ds.n_shards} shards (8 per bitwidth), {dt:.1f} s"}
+    return model, dec
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this path has no multi-GPU code (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU (no CPU fallback exists)", file=sys.stderr)
+        sys.exit(2)
+    import paper_2207_05022_amd as P
+    from paper_2207_05022_amd import device as D
+    import sti_synth as S
+
+    model, (wl, _) = bench_model(P, D, torch, S, args.steps, args.warmup)
+    decode, ds = bench_decode(P, torch, S, args.steps, args.warmup)
+    line = {
+        "metric": METRIC, "value": round(model["tokens_per_s"], 1), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(model["ms_per_step"], 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f16", "data": "synthetic",
+        "config": {"workload": "config4: BERT-base 12 layers, batch 32 x seq 128, bitwidths U{2,3,4,6,32}, full shard set, fp16 activations",
+                   "tokens_per_step": wl.tokens, "precision": "STI_PREC_F16_MFMA",
+                   "device": torch.cuda.get_device_name(0)},
+        "whole_path_tflops": round(model["whole_path_tflops"], 2),
+        "roofline": model["roofline"],
+        "kernel_ms_per_step": model["kernel_ms_per_step"],
+        "decode": decode,
+    }
+    if not args.no_cpu_baseline:
+        cpu_model, cpu_dec = cpu_baselines(S, wl, ds)
+        line["cpu_baseline"] = cpu_model
+        line["decode"]["cpu_baseline"] = cpu_dec
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -74,8 +74,9 @@ typedef enum { STI_F32 = 0, STI_F16 = 1, STI_BF16 = 2 } sti_dtype;
 /* STI_PREC_F32: float32 storage and arithmetic end to end (decode to a float32
  *   working buffer, then float32 kernels); any dimensions.
  * STI_PREC_F16_MFMA: binary16 operands on the matrix cores with float32
- *   accumulation, decode fused into the weight loader; needs d_model, d_head
- *   and ffn_per_shard to be multiples of 64 and seq <= 512. */
+ *   accumulation, decode fused into the weight loader; needs d_head == 64,
+ *   d_model and ffn_per_shard multiples of 64 and seq <= 512 (STI_ERR_DIMS
+ *   otherwise). */
 typedef enum { STI_PREC_F32 = 0, STI_PREC_F16_MFMA = 1 } sti_precision;
 
 typedef struct {
@@ -181,6 +182,35 @@ sti_status sti_model_forward(const sti_dims *dims, int n_layers, const sti_shard
                              void *y, sti_dtype io_dtype, int batch, int seq,
                              sti_precision precision, void *workspace, size_t workspace_bytes,
                              void *hip_stream);
+
+/* ---------------------------------------------------------------------------
+ * Per-kernel timing (the counterpart of the paper's one-time hardware profiling
+ * of computation delays, Section "Prerequisite: offline profiling").  Between
+ * sti_profile_begin() and sti_profile_end() every kernel launch of the entry
+ * points above is bracketed by two events on the caller's stream;
+ * sti_profile_end() waits for them and returns, per kernel class, the number
+ * of launches and the summed event-to-event time in milliseconds.  Process
+ * wide, not re-entrant; meant for measurement runs, not for production calls.
+ * ------------------------------------------------------------------------- */
+typedef enum {
+    STI_K_DECODE = 0,
+    STI_K_GEMM_QKV = 1,
+    STI_K_ATTENTION = 2,
+    STI_K_GEMM_OUT = 3,
+    STI_K_LAYERNORM = 4,
+    STI_K_GEMM_FFN_UP = 5,
+    STI_K_GEMM_FFN_DOWN = 6,
+    STI_K_CONVERT = 7,
+    STI_K_COUNT = 8
+} sti_kernel_class;
+
+typedef struct {
+    uint64_t launches[STI_K_COUNT];
+    double ms[STI_K_COUNT];
+} sti_profile;
+
+sti_status sti_profile_begin(void);
+sti_status sti_profile_end(sti_profile *out); /* HOST out */
 
 #ifdef __cplusplus
 }

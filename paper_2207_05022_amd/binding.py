@@ -34,6 +34,14 @@ class StiLayerParams(C.Structure):
                 ("bq", "bk", "bv", "bo", "b1", "b2", "ln1_g", "ln1_b", "ln2_g", "ln2_b")]
 
 
+KERNEL_CLASSES = ("decode", "gemm_qkv", "attention", "gemm_out", "layernorm", "gemm_ffn_up",
+                  "gemm_ffn_down", "convert")
+
+
+class StiProfile(C.Structure):
+    _fields_ = [("launches", C.c_uint64 * 8), ("ms", C.c_double * 8)]
+
+
 class StiError(RuntimeError):
     def __init__(self, status: int, where: str):
         self.status = status
@@ -65,6 +73,10 @@ def _load():
             C.POINTER(StiDims), C.c_int, C.POINTER(StiShard), C.POINTER(StiLayerParams),
             C.POINTER(C.c_int8), C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int,
             C.c_void_p, C.c_size_t, C.c_void_p]
+    L.sti_profile_begin.restype = C.c_int
+    L.sti_profile_begin.argtypes = []
+    L.sti_profile_end.restype = C.c_int
+    L.sti_profile_end.argtypes = [C.POINTER(StiProfile)]
     return L
 
 
@@ -196,3 +208,18 @@ def sti_model_forward(dims, store, params: Sequence, plan, x, y, precision: int,
                                ws_bytes, _stream_handle(stream))
     if st != 0:
         raise StiError(st, "sti_model_forward")
+
+
+def sti_profile_begin() -> None:
+    st = lib.sti_profile_begin()
+    if st != 0:
+        raise StiError(st, "sti_profile_begin")
+
+
+def sti_profile_end() -> dict:
+    """Returns {kernel class: (launches, total milliseconds)}."""
+    prof = StiProfile()
+    st = lib.sti_profile_end(C.byref(prof))
+    if st != 0:
+        raise StiError(st, "sti_profile_end")
+    return {name: (int(prof.launches[i]), float(prof.ms[i])) for i, name in enumerate(KERNEL_CLASSES)}

@@ -2,6 +2,7 @@
 // Every check runs before the first launch; device work goes to the caller's stream.
 #include <mutex>
 #include <new>
+#include <stdlib.h>
 #include <string.h>
 #include <vector>
 
@@ -69,6 +70,87 @@ StagingRing &staging()
     return ring;
 }
 
+// Optional per-launch timing: while enabled, every kernel launch is bracketed
+// by two events on the caller's stream; sti_profile_end() sums them per class.
+class Profiler {
+public:
+    bool enabled() const { return on_; }
+    hipError_t begin()
+    {
+        std::lock_guard<std::mutex> lock(mu_);
+        used_ = 0;
+        on_ = true;
+        return hipSuccess;
+    }
+    hipError_t mark(int cls, hipStream_t stream, bool start)
+    {
+        std::lock_guard<std::mutex> lock(mu_);
+        if (!on_) return hipSuccess;
+        if (start) {
+            if (used_ == recs_.size()) {
+                Rec r;
+                r.cls = cls;
+                hipError_t e = hipEventCreate(&r.a);
+                if (e != hipSuccess) return e;
+                e = hipEventCreate(&r.b);
+                if (e != hipSuccess) return e;
+                recs_.push_back(r);
+            }
+            recs_[used_].cls = cls;
+            return hipEventRecord(recs_[used_].a, stream);
+        }
+        hipError_t e = hipEventRecord(recs_[used_].b, stream);
+        ++used_;
+        return e;
+    }
+    hipError_t end(sti_profile *out)
+    {
+        std::lock_guard<std::mutex> lock(mu_);
+        on_ = false;
+        memset(out, 0, sizeof(*out));
+        for (size_t i = 0; i < used_; ++i) {
+            hipError_t e = hipEventSynchronize(recs_[i].b);
+            if (e != hipSuccess) return e;
+            float ms = 0.f;
+            e = hipEventElapsedTime(&ms, recs_[i].a, recs_[i].b);
+            if (e != hipSuccess) return e;
+            out->launches[recs_[i].cls] += 1;
+            out->ms[recs_[i].cls] += ms;
+        }
+        used_ = 0;
+        return hipSuccess;
+    }
+
+private:
+    struct Rec {
+        hipEvent_t a = nullptr, b = nullptr;
+        int cls = 0;
+    };
+    std::mutex mu_;
+    std::vector<Rec> recs_;
+    size_t used_ = 0;
+    bool on_ = false;
+};
+
+Profiler &profiler()
+{
+    static Profiler p;
+    return p;
+}
+
+// Launch `fn` (returns hipError_t), bracketed by profiling events when enabled.
+template <typename F>
+hipError_t timed(int cls, hipStream_t stream, F fn)
+{
+    Profiler &pr = profiler();
+    if (!pr.enabled()) return fn();
+    hipError_t e = pr.mark(cls, stream, true);
+    if (e != hipSuccess) return e;
+    e = fn();
+    hipError_t e2 = pr.mark(cls, stream, false);
+    return e != hipSuccess ? e : e2;
+}
+
 sti_status check_decode_shard(const sti_shard &s)
 {
     const int b = s.bitwidth;
@@ -89,7 +171,7 @@ sti_status check_decode_shard(const sti_shard &s)
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 struct WorkspaceLayout {
-    size_t w32 = 0, act[2] = {0, 0}, qkv = 0, ctx = 0, pre = 0, h = 0, u = 0, total = 0;
+    size_t w32 = 0, w16 = 0, act[2] = {0, 0}, qkv = 0, ctx = 0, pre = 0, h = 0, u = 0, total = 0;
 };
 
 // Offsets of the scratch regions of one layer call (sized for all M shards present).
@@ -105,6 +187,7 @@ WorkspaceLayout workspace_layout(const sti_dims &d, int64_t T, sti_precision pre
         return at;
     };
     if (prec == STI_PREC_F32) L.w32 = take(M * dm * (4 * dh + 2 * f) * 4);
+    else L.w16 = take(M * dm * (4 * dh + 2 * f) * 2);
     L.act[0] = take((size_t)T * dm * es);
     L.act[1] = take((size_t)T * dm * es);
     L.qkv = take((size_t)T * M * 3 * dh * es);
@@ -162,6 +245,16 @@ inline const void *block_start(const sti_shard &s, size_t elem_off)
     return (const uint8_t *)s.data + elem_off * (size_t)s.bitwidth / 8;
 }
 
+inline int predecode_min_tokens()
+{
+    static int v = -1;
+    if (v < 0) {
+        const char *e = getenv("STI_EXP_PREDECODE");
+        v = e ? atoi(e) : (1 << 30);
+    }
+    return v;
+}
+
 #define STI_TRY(expr)                          \
     do {                                       \
         if ((expr) != hipSuccess) return STI_ERR_HIP; \
@@ -188,6 +281,18 @@ sti_status run_layer(const sti_dims &d, const sti_shard *shards, const sti_layer
     memset(&bq, 0, sizeof(bq)); memset(&bo, 0, sizeof(bo));
     memset(&b1, 0, sizeof(b1)); memset(&b2, 0, sizeof(b2));
     const bool f32 = (prec == STI_PREC_F32);
+    // MFMA path: with many row tiles per weight it is cheaper to decompress the layer
+    // once into a binary16 working buffer than to decode inside every row tile
+    const bool predecode = !f32 && m > 0 && T >= predecode_min_tokens();
+    if (predecode) {
+        InlineShardTable t;
+        memset(&t, 0, sizeof(t));
+        for (int p = 0; p < m; ++p) {
+            const sti_shard &s = shards[present[p]];
+            t.d[p] = ShardDesc{s.data, s.codebook, s.bitwidth, present[p]};
+        }
+        STI_TRY(timed(STI_K_DECODE, stream, [&] { return launch_decode(nullptr, &t, m, wsh, ws + wl.w16, STI_F16, stream); }));
+    }
     if (f32 && m > 0) {
         InlineShardTable t;
         memset(&t, 0, sizeof(t));
@@ -195,7 +300,7 @@ sti_status run_layer(const sti_dims &d, const sti_shard *shards, const sti_layer
             const sti_shard &s = shards[present[p]];
             t.d[p] = ShardDesc{s.data, s.codebook, s.bitwidth, present[p]};
         }
-        STI_TRY(launch_decode(nullptr, &t, m, wsh, ws + wl.w32, STI_F32, stream));
+        STI_TRY(timed(STI_K_DECODE, stream, [&] { return launch_decode(nullptr, &t, m, wsh, ws + wl.w32, STI_F32, stream); }));
     }
     for (int p = 0; p < m; ++p) {
         const sti_shard &s = shards[present[p]];
@@ -205,6 +310,12 @@ sti_status run_layer(const sti_dims &d, const sti_shard *shards, const sti_layer
             bo.b[p] = GemmBlock{w + off_o, nullptr, 32, present[p]};
             b1.b[p] = GemmBlock{w + off_1, nullptr, 32, present[p]};
             b2.b[p] = GemmBlock{w + off_2, nullptr, 32, present[p]};
+        } else if (predecode) {
+            const _Float16 *w = (const _Float16 *)(ws + wl.w16) + (size_t)p * wsh;
+            bq.b[p] = GemmBlock{w, nullptr, 16, present[p]};
+            bo.b[p] = GemmBlock{w + off_o, nullptr, 16, present[p]};
+            b1.b[p] = GemmBlock{w + off_1, nullptr, 16, present[p]};
+            b2.b[p] = GemmBlock{w + off_2, nullptr, 16, present[p]};
         } else {
             bq.b[p] = GemmBlock{block_start(s, 0), s.codebook, s.bitwidth, present[p]};
             bo.b[p] = GemmBlock{block_start(s, off_o), s.codebook, s.bitwidth, present[p]};
@@ -216,7 +327,16 @@ sti_status run_layer(const sti_dims &d, const sti_shard *shards, const sti_layer
     float *pre = (float *)(ws + wl.pre);
     const sti_dtype act_dtype = f32 ? STI_F32 : STI_F16;
     auto gemm = [&](const GemmProblem &p, const GemmBlocks &blk) {
-        return f32 ? launch_gemm_f32(p, blk, stream) : launch_gemm_mfma(p, blk, stream);
+        static const int cls[4] = {STI_K_GEMM_QKV, STI_K_GEMM_FFN_UP, STI_K_GEMM_OUT,
+                                   STI_K_GEMM_FFN_DOWN};
+        return timed(cls[p.kind], stream, [&] {
+            return f32 ? launch_gemm_f32(p, blk, stream) : launch_gemm_mfma(p, blk, stream);
+        });
+    };
+    auto layernorm = [&](void *dst, sti_dtype dt, const float *g, const float *b) {
+        return timed(STI_K_LAYERNORM, stream, [&] {
+            return launch_layernorm(pre, dst, dt, g, b, T, dm, d.ln_eps, stream);
+        });
     };
 
     GemmProblem p;
@@ -226,14 +346,16 @@ sti_status run_layer(const sti_dims &d, const sti_shard *shards, const sti_layer
         p.d_head = dh; p.A = in; p.lda = dm; p.C = qkv; p.ldc = m * 3 * dh;
         p.bias0 = prm.bq; p.bias1 = prm.bk; p.bias2 = prm.bv;
         STI_TRY(gemm(p, bq));
-        if (f32) STI_TRY(launch_attention_f32((const float *)qkv, (float *)ctx, B, Lseq, m, dh, stream));
-        else STI_TRY(launch_attention_mfma(qkv, ctx, B, Lseq, m, dh, stream));
+        STI_TRY(timed(STI_K_ATTENTION, stream, [&] {
+            return f32 ? launch_attention_f32((const float *)qkv, (float *)ctx, B, Lseq, m, dh, stream)
+                       : launch_attention_mfma(qkv, ctx, B, Lseq, m, dh, stream);
+        }));
     }
     memset(&p, 0, sizeof(p));
     p.kind = GEMM_OUT; p.T = T; p.n_blocks = m; p.block_rows = dm; p.block_cols = dh; p.d_head = dh;
     p.A = ctx; p.lda = m * dh; p.C = pre; p.ldc = dm; p.bias0 = prm.bo; p.resid = in; p.ldr = dm;
     STI_TRY(gemm(p, bo));
-    STI_TRY(launch_layernorm(pre, h, act_dtype, prm.ln1_g, prm.ln1_b, T, dm, d.ln_eps, stream));
+    STI_TRY(layernorm(h, act_dtype, prm.ln1_g, prm.ln1_b));
     if (m > 0) {
         memset(&p, 0, sizeof(p));
         p.kind = GEMM_FFN_UP; p.T = T; p.n_blocks = m; p.block_rows = f; p.block_cols = dm;
@@ -245,7 +367,7 @@ sti_status run_layer(const sti_dims &d, const sti_shard *shards, const sti_layer
     p.d_head = dh; p.A = u; p.lda = m * f; p.C = pre; p.ldc = dm; p.bias0 = prm.b2; p.resid = h;
     p.ldr = dm;
     STI_TRY(gemm(p, b2));
-    STI_TRY(launch_layernorm(pre, out, out_dtype, prm.ln2_g, prm.ln2_b, T, dm, d.ln_eps, stream));
+    STI_TRY(layernorm(out, out_dtype, prm.ln2_g, prm.ln2_b));
     return STI_OK;
 }
 
@@ -326,14 +448,18 @@ sti_status sti_decode_shards(const sti_shard *shards, int n_shards, uint64_t wei
             table[s] = ShardDesc{shards[s].data, shards[s].codebook, shards[s].bitwidth, s};
         e = staging().upload(table.data(), table.size(), workspace, stream);
         if (e != hipSuccess) return STI_ERR_HIP;
-        e = launch_decode((const ShardDesc *)workspace, nullptr, n_shards, weights_per_shard, out,
-                          out_dtype, stream);
+        e = timed(STI_K_DECODE, stream, [&] {
+            return launch_decode((const ShardDesc *)workspace, nullptr, n_shards, weights_per_shard,
+                                 out, out_dtype, stream);
+        });
     } else {
         InlineShardTable t;
         memset(&t, 0, sizeof(t));
         for (int s = 0; s < n_shards; ++s)
             t.d[s] = ShardDesc{shards[s].data, shards[s].codebook, shards[s].bitwidth, s};
-        e = launch_decode(nullptr, &t, n_shards, weights_per_shard, out, out_dtype, stream);
+        e = timed(STI_K_DECODE, stream, [&] {
+            return launch_decode(nullptr, &t, n_shards, weights_per_shard, out, out_dtype, stream);
+        });
     }
     return e == hipSuccess ? STI_OK : STI_ERR_HIP;
 }
@@ -376,7 +502,7 @@ sti_status sti_layer_forward(const sti_dims *dims, const sti_shard *shards,
     const sti_dtype act = (precision == STI_PREC_F32) ? STI_F32 : STI_F16;
     const void *in = x;
     if (io_dtype != act) {
-        STI_TRY(launch_convert(x, io_dtype, ws + wl.act[0], act, (uint64_t)T * dims->d_model, stream));
+        STI_TRY(timed(STI_K_CONVERT, stream, [&] { return launch_convert(x, io_dtype, ws + wl.act[0], act, (uint64_t)T * dims->d_model, stream); }));
         in = ws + wl.act[0];
     }
     return run_layer(*dims, shards, *params, in, y, io_dtype, batch, seq, precision, ws, wl, stream);
@@ -438,7 +564,7 @@ sti_status sti_model_forward(const sti_dims *dims, int n_layers, const sti_shard
     const void *cur = x;
     int next_buf = 0;
     if (io_dtype != act) {
-        STI_TRY(launch_convert(x, io_dtype, ws + wl.act[0], act, (uint64_t)T * dims->d_model, stream));
+        STI_TRY(timed(STI_K_CONVERT, stream, [&] { return launch_convert(x, io_dtype, ws + wl.act[0], act, (uint64_t)T * dims->d_model, stream); }));
         cur = ws + wl.act[0];
         next_buf = 1;
     }
@@ -452,6 +578,17 @@ sti_status sti_model_forward(const sti_dims *dims, int n_layers, const sti_shard
         next_buf ^= 1;
     }
     return STI_OK;
+}
+
+sti_status sti_profile_begin(void)
+{
+    return profiler().begin() == hipSuccess ? STI_OK : STI_ERR_HIP;
+}
+
+sti_status sti_profile_end(sti_profile *out)
+{
+    if (!out) return STI_ERR_NULL;
+    return profiler().end(out) == hipSuccess ? STI_OK : STI_ERR_HIP;
 }
 
 }  // extern "C"
