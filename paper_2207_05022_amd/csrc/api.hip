@@ -291,7 +291,7 @@ sti_status run_layer(const sti_dims &d, const sti_shard *shards, const sti_layer
             const sti_shard &s = shards[present[p]];
             t.d[p] = ShardDesc{s.data, s.codebook, s.bitwidth, present[p]};
         }
-        STI_TRY(timed(STI_K_DECODE, stream, [&] { return launch_decode(nullptr, &t, m, wsh, ws + wl.w16, STI_F16, stream); }));
+        STI_TRY(timed(STI_K_DECODE, stream, [&] { return launch_decode_tiled(t, m, dm, dh, f, ws + wl.w16, stream); }));
     }
     if (f32 && m > 0) {
         InlineShardTable t;
@@ -312,10 +312,10 @@ sti_status run_layer(const sti_dims &d, const sti_shard *shards, const sti_layer
             b2.b[p] = GemmBlock{w + off_2, nullptr, 32, present[p]};
         } else if (predecode) {
             const _Float16 *w = (const _Float16 *)(ws + wl.w16) + (size_t)p * wsh;
-            bq.b[p] = GemmBlock{w, nullptr, 16, present[p]};
-            bo.b[p] = GemmBlock{w + off_o, nullptr, 16, present[p]};
-            b1.b[p] = GemmBlock{w + off_1, nullptr, 16, present[p]};
-            b2.b[p] = GemmBlock{w + off_2, nullptr, 16, present[p]};
+            bq.b[p] = GemmBlock{w, nullptr, 17, present[p]};
+            bo.b[p] = GemmBlock{w + off_o, nullptr, 17, present[p]};
+            b1.b[p] = GemmBlock{w + off_1, nullptr, 17, present[p]};
+            b2.b[p] = GemmBlock{w + off_2, nullptr, 17, present[p]};
         } else {
             bq.b[p] = GemmBlock{block_start(s, 0), s.codebook, s.bitwidth, present[p]};
             bo.b[p] = GemmBlock{block_start(s, off_o), s.codebook, s.bitwidth, present[p]};
@@ -333,9 +333,12 @@ sti_status run_layer(const sti_dims &d, const sti_shard *shards, const sti_layer
             return f32 ? launch_gemm_f32(p, blk, stream) : launch_gemm_mfma(p, blk, stream);
         });
     };
-    auto layernorm = [&](void *dst, sti_dtype dt, const float *g, const float *b) {
+    // the MFMA GEMMs leave bias and residual to the LayerNorm kernel
+    auto layernorm = [&](void *dst, sti_dtype dt, const float *g, const float *b,
+                         const float *bias, const void *resid) {
         return timed(STI_K_LAYERNORM, stream, [&] {
-            return launch_layernorm(pre, dst, dt, g, b, T, dm, d.ln_eps, stream);
+            return launch_layernorm(pre, f32 ? nullptr : bias, f32 ? nullptr : resid, dst, dt, g, b,
+                                    T, dm, d.ln_eps, stream);
         });
     };
 
@@ -355,7 +358,7 @@ sti_status run_layer(const sti_dims &d, const sti_shard *shards, const sti_layer
     p.kind = GEMM_OUT; p.T = T; p.n_blocks = m; p.block_rows = dm; p.block_cols = dh; p.d_head = dh;
     p.A = ctx; p.lda = m * dh; p.C = pre; p.ldc = dm; p.bias0 = prm.bo; p.resid = in; p.ldr = dm;
     STI_TRY(gemm(p, bo));
-    STI_TRY(layernorm(h, act_dtype, prm.ln1_g, prm.ln1_b));
+    STI_TRY(layernorm(h, act_dtype, prm.ln1_g, prm.ln1_b, prm.bo, in));
     if (m > 0) {
         memset(&p, 0, sizeof(p));
         p.kind = GEMM_FFN_UP; p.T = T; p.n_blocks = m; p.block_rows = f; p.block_cols = dm;
@@ -367,7 +370,7 @@ sti_status run_layer(const sti_dims &d, const sti_shard *shards, const sti_layer
     p.d_head = dh; p.A = u; p.lda = m * f; p.C = pre; p.ldc = dm; p.bias0 = prm.b2; p.resid = h;
     p.ldr = dm;
     STI_TRY(gemm(p, b2));
-    STI_TRY(layernorm(out, out_dtype, prm.ln2_g, prm.ln2_b));
+    STI_TRY(layernorm(out, out_dtype, prm.ln2_g, prm.ln2_b, prm.b2, h));
     return STI_OK;
 }
 

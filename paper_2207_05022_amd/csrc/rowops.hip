@@ -41,28 +41,102 @@ template <> struct Elem<STI_BF16> {
     static __device__ inline void store(uint16_t *p, float v) { *p = f32_to_bf16_bits(v); }
 };
 
-// One wave per row; two-pass mean / variance in float32.
+// v[t][:] = pre[t][:] (+ bias[:]) (+ resid[t][:]);  y[t][:] = LayerNorm(v) * g + b.
+// One wave per row; two-pass mean / variance in float32.  General sizes.
 template <int DT>
-__global__ __launch_bounds__(256) void layernorm_kernel(const float *pre, typename Elem<DT>::type *y,
-                                                        const float *g, const float *b, int T, int d,
-                                                        float eps)
+__global__ __launch_bounds__(256) void layernorm_kernel(const float *pre, const float *bias,
+                                                        const _Float16 *resid,
+                                                        typename Elem<DT>::type *y, const float *g,
+                                                        const float *b, int T, int d, float eps)
 {
     const int row = blockIdx.x * 4 + threadIdx.x / 64;
     const int lane = threadIdx.x % 64;
     if (row >= T) return;
     const float *r = pre + (int64_t)row * d;
+    const _Float16 *rs = resid ? resid + (int64_t)row * d : nullptr;
+    auto value = [&](int c) {
+        float v = r[c];
+        if (bias) v += bias[c];
+        if (rs) v += (float)rs[c];
+        return v;
+    };
     float s = 0.f;
-    for (int c = lane; c < d; c += 64) s += r[c];
+    for (int c = lane; c < d; c += 64) s += value(c);
     const float mean = wave_sum(s) / (float)d;
     float q = 0.f;
     for (int c = lane; c < d; c += 64) {
-        float t = r[c] - mean;
+        float t = value(c) - mean;
         q = fmaf(t, t, q);
     }
     const float var = wave_sum(q) / (float)d;
     const float inv = 1.0f / sqrtf(var + eps);
     typename Elem<DT>::type *o = y + (int64_t)row * d;
-    for (int c = lane; c < d; c += 64) Elem<DT>::store(o + c, (r[c] - mean) * inv * g[c] + b[c]);
+    for (int c = lane; c < d; c += 64) Elem<DT>::store(o + c, (value(c) - mean) * inv * g[c] + b[c]);
+}
+
+// Same, for d a multiple of 4 and at most 2048: the row is read once with 16-byte loads
+// and kept in registers.
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 half4 __attribute__((ext_vector_type(4)));
+
+template <int DT>
+__global__ __launch_bounds__(256) void layernorm_vec_kernel(const float *pre, const float *bias,
+                                                            const _Float16 *resid,
+                                                            typename Elem<DT>::type *y,
+                                                            const float *g, const float *b, int T,
+                                                            int d, float eps)
+{
+    constexpr int MAXC = 8;
+    const int row = blockIdx.x * 4 + threadIdx.x / 64;
+    const int lane = threadIdx.x % 64;
+    if (row >= T) return;
+    const int nchunk = d >> 2;
+    const f32x4 *r = (const f32x4 *)(pre + (int64_t)row * d);
+    f32x4 v[MAXC];
+    float s = 0.f;
+#pragma unroll
+    for (int j = 0; j < MAXC; ++j) {
+        const int c = lane + 64 * j;
+        v[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+        if (c < nchunk) {
+            f32x4 x = r[c];
+            if (bias) x += ((const f32x4 *)bias)[c];
+            if (resid) {
+                half4 h = ((const half4 *)(resid + (int64_t)row * d))[c];
+                x += f32x4{(float)h.x, (float)h.y, (float)h.z, (float)h.w};
+            }
+            v[j] = x;
+            s += (x.x + x.y) + (x.z + x.w);
+        }
+    }
+    const float mean = wave_sum(s) / (float)d;
+    float q = 0.f;
+#pragma unroll
+    for (int j = 0; j < MAXC; ++j) {
+        if (lane + 64 * j < nchunk) {
+            f32x4 t = v[j] - mean;
+            q += (t.x * t.x + t.y * t.y) + (t.z * t.z + t.w * t.w);
+        }
+    }
+    const float var = wave_sum(q) / (float)d;
+    const float inv = 1.0f / sqrtf(var + eps);
+    typename Elem<DT>::type *o = y + (int64_t)row * d;
+#pragma unroll
+    for (int j = 0; j < MAXC; ++j) {
+        const int c = lane + 64 * j;
+        if (c < nchunk) {
+            const f32x4 gg = ((const f32x4 *)g)[c], bb = ((const f32x4 *)b)[c];
+            const f32x4 t = (v[j] - mean) * inv * gg + bb;
+            if constexpr (DT == STI_F32) {
+                ((f32x4 *)o)[c] = t;
+            } else if constexpr (DT == STI_F16) {
+                ((half4 *)o)[c] = half4{(_Float16)t.x, (_Float16)t.y, (_Float16)t.z, (_Float16)t.w};
+            } else {
+                Elem<DT>::store(o + 4 * c, t.x); Elem<DT>::store(o + 4 * c + 1, t.y);
+                Elem<DT>::store(o + 4 * c + 2, t.z); Elem<DT>::store(o + 4 * c + 3, t.w);
+            }
+        }
+    }
 }
 
 template <int SRC, int DST>
@@ -95,21 +169,30 @@ hipError_t convert_from(const void *src, void *dst, sti_dtype dst_dtype, uint64_
 
 }  // namespace
 
-hipError_t launch_layernorm(const float *pre, void *y, sti_dtype out_dtype, const float *g,
-                            const float *b, int T, int d, float eps, hipStream_t stream)
+template <int DT>
+void launch_ln_typed(const float *pre, const float *bias, const void *resid, void *y, const float *g,
+                     const float *b, int T, int d, float eps, bool vec, hipStream_t stream)
+{
+    typedef typename Elem<DT>::type O;
+    dim3 grid((T + 3) / 4);
+    if (vec)
+        layernorm_vec_kernel<DT><<<grid, 256, 0, stream>>>(pre, bias, (const _Float16 *)resid, (O *)y, g, b, T, d, eps);
+    else
+        layernorm_kernel<DT><<<grid, 256, 0, stream>>>(pre, bias, (const _Float16 *)resid, (O *)y, g, b, T, d, eps);
+}
+
+hipError_t launch_layernorm(const float *pre, const float *bias, const void *resid_f16, void *y,
+                            sti_dtype out_dtype, const float *g, const float *b, int T, int d,
+                            float eps, hipStream_t stream)
 {
     if (T <= 0 || d <= 0) return hipSuccess;
-    dim3 grid((T + 3) / 4);
+    auto al16 = [](const void *p) { return ((uintptr_t)p & 15) == 0; };
+    const bool vec = d % 4 == 0 && d <= 2048 && al16(pre) && al16(g) && al16(b) && al16(y) &&
+                     (!bias || al16(bias)) && (!resid_f16 || al16(resid_f16));
     switch (out_dtype) {
-        case STI_F32:
-            layernorm_kernel<STI_F32><<<grid, 256, 0, stream>>>(pre, (float *)y, g, b, T, d, eps);
-            break;
-        case STI_F16:
-            layernorm_kernel<STI_F16><<<grid, 256, 0, stream>>>(pre, (_Float16 *)y, g, b, T, d, eps);
-            break;
-        case STI_BF16:
-            layernorm_kernel<STI_BF16><<<grid, 256, 0, stream>>>(pre, (uint16_t *)y, g, b, T, d, eps);
-            break;
+        case STI_F32: launch_ln_typed<STI_F32>(pre, bias, resid_f16, y, g, b, T, d, eps, vec, stream); break;
+        case STI_F16: launch_ln_typed<STI_F16>(pre, bias, resid_f16, y, g, b, T, d, eps, vec, stream); break;
+        case STI_BF16: launch_ln_typed<STI_BF16>(pre, bias, resid_f16, y, g, b, T, d, eps, vec, stream); break;
     }
     return hipGetLastError();
 }

@@ -27,6 +27,11 @@ struct InlineShardTable {
 hipError_t launch_decode(const ShardDesc *table, const InlineShardTable *inline_table, int n_shards,
                          uint64_t n, void *out, sti_dtype out_dtype, hipStream_t stream);
 
+// Decode n_shards shards of a layer (d, dh, f geometry) into the fragment-tiled binary16
+// working buffer out[n_shards][Wsh] used by the matrix-core GEMM (see weight_loader.hpp).
+hipError_t launch_decode_tiled(const InlineShardTable &table, int n_shards, int d, int dh, int f,
+                               void *out, hipStream_t stream);
+
 // ---- layer kernels ----------------------------------------------------------
 // The four projections of a layer over its present shards, seen as GEMMs
 // C[T x N] = A[T x K] * W^T whose weight operand is cut into per-shard blocks:
@@ -40,7 +45,7 @@ enum GemmKind : int32_t {
 struct GemmBlock {
     const void *w;          // start of the block's weights: float32 values, or a k-bit stream
     const float *codebook;  // centroids when bits <= 6
-    int32_t bits;           // 2..6, 32
+    int32_t bits;           // 2..6, 32; 17 = fragment-tiled binary16 working buffer
     int32_t shard;          // original shard id (selects the bias slice)
 };
 
@@ -70,17 +75,20 @@ hipError_t launch_gemm_f32(const GemmProblem &p, const GemmBlocks &blocks, hipSt
 hipError_t launch_attention_f32(const float *qkv, float *ctx, int B, int L, int m, int dh,
                                 hipStream_t stream);
 
-// binary16 MFMA path (gemm_mfma.hip, attention_mfma.hip): A is binary16; C is
-// binary16 for QKV / FFN_UP and float32 (pre-LayerNorm) for OUT / FFN_DOWN;
-// resid is binary16; weights are decoded inside the loader.
+// binary16 MFMA path (gemm_mfma.hip, attention_mfma.hip): A is binary16; C is binary16
+// (bias, GELU applied) for QKV / FFN_UP and the raw float32 sums for OUT / FFN_DOWN, whose
+// bias and residual are added by launch_layernorm; weights are decoded inside the loader
+// or come from the fragment-tiled working buffer.
 hipError_t launch_gemm_mfma(const GemmProblem &p, const GemmBlocks &blocks, hipStream_t stream);
 hipError_t launch_attention_mfma(const void *qkv, void *ctx, int B, int L, int m, int dh,
                                  hipStream_t stream);
 
 // rowops.hip
-// y[t][:] = LayerNorm(pre[t][:]) * g + b; pre float32 [T x d]; y of out_dtype.
-hipError_t launch_layernorm(const float *pre, void *y, sti_dtype out_dtype, const float *g,
-                            const float *b, int T, int d, float eps, hipStream_t stream);
+// y[t][:] = LayerNorm(pre[t][:] + bias[:] + resid[t][:]) * g + b; pre float32 [T x d];
+// bias (float32 [d]) and resid_f16 (binary16 [T x d]) may be NULL; y of out_dtype.
+hipError_t launch_layernorm(const float *pre, const float *bias, const void *resid_f16, void *y,
+                            sti_dtype out_dtype, const float *g, const float *b, int T, int d,
+                            float eps, hipStream_t stream);
 // elementwise conversion between activation types
 hipError_t launch_convert(const void *src, sti_dtype src_dtype, void *dst, sti_dtype dst_dtype,
                           uint64_t n, hipStream_t stream);
