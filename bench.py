@@ -164,6 +164,8 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 1 GiB device copy (reference for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this path has no multi-GPU code (run with --gpus 1)", file=sys.stderr)
@@ -176,6 +178,13 @@ def main():
     from paper_2207_05022_amd import device as D
     import sti_synth as S
 
+    if args.calibrate_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").random_(0, 256)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     model, (wl, _) = bench_model(P, D, torch, S, args.steps, args.warmup)
     decode, ds = bench_decode(P, torch, S, args.steps, args.warmup)
     line = {

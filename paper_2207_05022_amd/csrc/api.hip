@@ -2,7 +2,6 @@
 // Every check runs before the first launch; device work goes to the caller's stream.
 #include <mutex>
 #include <new>
-#include <stdlib.h>
 #include <string.h>
 #include <vector>
 
@@ -245,15 +244,10 @@ inline const void *block_start(const sti_shard &s, size_t elem_off)
     return (const uint8_t *)s.data + elem_off * (size_t)s.bitwidth / 8;
 }
 
-inline int predecode_min_tokens()
-{
-    static int v = -1;
-    if (v < 0) {
-        const char *e = getenv("STI_EXP_PREDECODE");
-        v = e ? atoi(e) : (1 << 30);
-    }
-    return v;
-}
+// From this many tokens on, a layer's shards are decompressed once into the binary16
+// working buffer; below it, the GEMMs decode the streams themselves (every weight is then
+// used by at most a few row tiles).
+constexpr int kWorkingBufferMinTokens = 512;
 
 #define STI_TRY(expr)                          \
     do {                                       \
@@ -283,7 +277,7 @@ sti_status run_layer(const sti_dims &d, const sti_shard *shards, const sti_layer
     const bool f32 = (prec == STI_PREC_F32);
     // MFMA path: with many row tiles per weight it is cheaper to decompress the layer
     // once into a binary16 working buffer than to decode inside every row tile
-    const bool predecode = !f32 && m > 0 && T >= predecode_min_tokens();
+    const bool predecode = !f32 && m > 0 && T >= kWorkingBufferMinTokens;
     if (predecode) {
         InlineShardTable t;
         memset(&t, 0, sizeof(t));

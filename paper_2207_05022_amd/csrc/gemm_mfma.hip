@@ -20,7 +20,6 @@
 //     product does not see;
 //   - binary16 results leave through LDS so that every global store is 16 bytes of
 //     one output row.
-#include <stdlib.h>
 #include "sti_internal.hpp"
 #include "weight_loader.hpp"
 
@@ -278,15 +277,10 @@ hipError_t launch_gemm_mfma(const GemmProblem &p, const GemmBlocks &blocks, hipS
     if (p.T <= 0 || N <= 0) return hipSuccess;
     if (N % 64 || p.block_rows % 64 || p.block_cols % BK || p.lda % 8 || p.ldc % 8)
         return hipErrorInvalidValue;
-    static int cfg = -1;
-    if (cfg < 0) { const char *e = getenv("STI_EXP_CFG"); cfg = e ? atoi(e) : 0; }
-    switch (cfg) {
-        case 1: return launch_cfg<4, 2, 1, 4>(p, blocks, N, stream);
-        case 2: return launch_cfg<2, 2, 2, 2>(p, blocks, N, stream);
-        case 3: return launch_cfg<4, 2, 2, 2>(p, blocks, N, stream);
-        case 4: return launch_cfg<2, 1, 1, 4>(p, blocks, N, stream);
-        default: return launch_cfg<4, 1, 1, 4>(p, blocks, N, stream);
-    }
+    // Wide outputs (QKV, FFN1) take 128-row tiles; the d-wide outputs (O, FFN2) take 64-row
+    // tiles so that the grid still covers the chip.
+    if (N >= 2048 && p.T > 64) return launch_cfg<4, 1, 1, 4>(p, blocks, N, stream);
+    return launch_cfg<2, 1, 1, 4>(p, blocks, N, stream);
 }
 
 }  // namespace sti

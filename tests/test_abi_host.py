@@ -1,0 +1,146 @@
+"""Host-side checks of the C ABI: the shared library loads, exports every entry point that
+include/sti.h declares, and rejects bad arguments before touching the device.  No kernel runs."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def P():
+    lib = os.path.join(ROOT, "paper_2207_05022_amd", "libsti.so")
+    if not os.path.exists(lib):
+        import importlib.util
+        spec = importlib.util.spec_from_file_location(
+            "_sti_build", os.path.join(ROOT, "paper_2207_05022_amd", "build.py"))
+        mod = importlib.util.module_from_spec(spec)
+        spec.loader.exec_module(mod)
+        mod.build()
+    import paper_2207_05022_amd as pkg
+    return pkg
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "sti.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(sti_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(P):
+    names = declared_functions()
+    assert {"sti_decode_shards", "sti_layer_forward", "sti_model_forward", "sti_workspace_bytes",
+            "sti_decode_workspace_bytes", "sti_status_string"} <= set(names)
+    for n in names:
+        assert hasattr(P.lib, n), n
+
+
+def test_status_strings(P):
+    seen = {P.status_string(i) for i in range(10)}
+    assert len(seen) == 10 and "ok" in seen
+    assert P.status_string(99) == "unknown status"
+
+
+FAKE = 0x1000  # aligned, never dereferenced: all checks below fail before any launch
+
+
+def shard(P, bits, data=FAKE, cb=FAKE, nout=0):
+    return P.StiShard(bits, data, cb, nout, None, None)
+
+
+def decode(P, shards, n=8, out=FAKE, dtype=1, ws=None, ws_bytes=0):
+    arr = (P.StiShard * max(1, len(shards)))(*shards)
+    return P.lib.sti_decode_shards(arr, len(shards), n, out, dtype, ws, ws_bytes, None)
+
+
+def test_decode_argument_errors(P):
+    assert decode(P, [shard(P, 7)]) == 3                      # bitwidth
+    assert decode(P, [shard(P, 0)]) == 3                      # absent is not decodable
+    assert decode(P, [shard(P, 1)]) == 3
+    assert decode(P, [shard(P, 4, data=None)]) == 4           # missing data
+    assert decode(P, [shard(P, 4, cb=None)]) == 4             # missing codebook
+    assert decode(P, [shard(P, 4, data=FAKE + 8)]) == 5       # stream alignment
+    assert decode(P, [shard(P, 4, cb=FAKE + 2)]) == 5
+    assert decode(P, [shard(P, 4)], out=FAKE + 4) == 5
+    assert decode(P, [shard(P, 4)], out=None) == 1
+    assert decode(P, [shard(P, 4)], dtype=5) == 7
+    assert decode(P, [shard(P, 4, nout=3)]) == 9              # outliers not implemented
+    assert P.lib.sti_decode_shards(None, 3, 8, FAKE, 1, None, 0, None) == 1
+    assert P.lib.sti_decode_shards(None, -1, 8, FAKE, 1, None, 0, None) == 2
+    assert P.lib.sti_decode_shards(None, 0, 8, FAKE, 1, None, 0, None) == 0
+    many = [shard(P, 3)] * 100
+    assert P.sti_decode_workspace_bytes(100) > 0 and P.sti_decode_workspace_bytes(64) == 0
+    assert decode(P, many) == 6                               # workspace missing
+    assert decode(P, many, ws=FAKE, ws_bytes=8) == 6          # workspace too small
+    assert decode(P, [shard(P, 32, cb=None)], n=0) == 0       # nothing to do
+
+
+class Dims:
+    def __init__(self, d=768, M=12, dh=64, f=256, eps=1e-12):
+        self.d_model, self.n_heads, self.d_head, self.ffn_per_shard, self.ln_eps = d, M, dh, f, eps
+
+
+def test_workspace_query(P):
+    assert P.sti_workspace_bytes(Dims(), 1, 128, P.STI_PREC_F32) > 12 * 589824 * 4
+    assert P.sti_workspace_bytes(Dims(), 32, 128, P.STI_PREC_F16_MFMA) > 0
+    assert P.sti_workspace_bytes(Dims(), 0, 128, P.STI_PREC_F32) >= 256
+    assert P.sti_workspace_bytes(Dims(d=0), 1, 8, 0) == 0
+    assert P.sti_workspace_bytes(Dims(M=65), 1, 8, 0) == 0
+    assert P.sti_workspace_bytes(Dims(), -1, 8, 0) == 0
+    assert P.sti_workspace_bytes(Dims(), 1, 8, 3) == 0
+    assert P.sti_workspace_bytes(Dims(dh=32), 1, 8, P.STI_PREC_F16_MFMA) == 0     # needs d_head 64
+    assert P.sti_workspace_bytes(Dims(d=100), 1, 8, P.STI_PREC_F16_MFMA) == 0
+    assert P.sti_workspace_bytes(Dims(), 1, 513, P.STI_PREC_F16_MFMA) == 0
+    assert P.sti_workspace_bytes(Dims(d=100, dh=10, f=7), 2, 9, P.STI_PREC_F32) > 0
+
+
+def layer(P, dims=None, shards=None, params="ok", x=FAKE, y=FAKE + 0x100000, io=0, batch=1, seq=8,
+          prec=0, ws=FAKE + 0x200000, ws_bytes=1 << 40):
+    d = P.binding.make_dims(dims or Dims(d=64, M=2, dh=64, f=64))
+    shards = shards if shards is not None else [shard(P, 4), shard(P, 0, None, None)]
+    arr = (P.StiShard * len(shards))(*shards)
+    prm = P.StiLayerParams(*([FAKE] * 10)) if params == "ok" else params
+    return P.lib.sti_layer_forward(C.byref(d), arr, C.byref(prm) if prm is not None else None, x, y, io,
+                                   batch, seq, prec, ws, ws_bytes, None)
+
+
+def test_layer_argument_errors(P):
+    assert layer(P, shards=[shard(P, 9), shard(P, 4)]) == 3
+    assert layer(P, shards=[shard(P, 4, data=None), shard(P, 4)]) == 4
+    assert layer(P, params=None) == 1
+    bad = P.StiLayerParams(*([FAKE] * 9 + [None]))
+    assert layer(P, params=bad) == 1
+    assert layer(P, x=None) == 1
+    assert layer(P, x=FAKE + 4) == 5
+    assert layer(P, y=FAKE) == 2                    # x and y alias
+    assert layer(P, io=7) == 7
+    assert layer(P, prec=2) == 7
+    assert layer(P, batch=-1) == 2
+    assert layer(P, ws=None) == 6
+    assert layer(P, ws_bytes=16) == 6
+    assert layer(P, ws=FAKE + 0x200010) == 5
+    assert layer(P, dims=Dims(d=64, M=2, dh=32, f=64), prec=1) == 2
+    assert layer(P, batch=0) == 0                   # empty batch: nothing to do
+
+
+def test_model_argument_errors(P):
+    d = P.binding.make_dims(Dims(d=64, M=2, dh=64, f=64))
+    store = (P.StiShard * 12)(*[shard(P, k) for k in (2, 3, 4, 5, 6, 32)] * 2)
+    prm = (P.StiLayerParams * 1)(P.StiLayerParams(*([FAKE] * 10)))
+
+    def call(plan, store=store, n_layers=1):
+        pl = np.asarray(plan, dtype=np.int8)
+        return P.lib.sti_model_forward(C.byref(d), n_layers, store, prm,
+                                       pl.ctypes.data_as(C.POINTER(C.c_int8)), FAKE, FAKE + 0x100000, 0,
+                                       1, 8, 0, None, 0, None)
+
+    assert call([4, 7]) == 3                        # plan bitwidth
+    assert call([4, 0]) == 6                        # valid plan, then workspace is missing
+    missing = (P.StiShard * 12)(*[shard(P, k, data=None) for k in (2, 3, 4, 5, 6, 32)] * 2)
+    assert call([4, 0], store=missing) == 4         # selected version not stored
+    wrong = (P.StiShard * 12)(*[shard(P, 5) for _ in range(12)])
+    assert call([4, 0], store=wrong) == 3           # slot holds another bitwidth
+    assert call([4, 0], n_layers=-1) == 2
