@@ -191,7 +191,11 @@ WorkspaceLayout workspace_layout(const sti_dims &d, int64_t T, sti_precision pre
     L.act[1] = take((size_t)T * dm * es);
     L.qkv = take((size_t)T * M * 3 * dh * es);
     L.ctx = take((size_t)T * M * dh * es);
-    L.pre = take((size_t)T * dm * 4);
+    {   // float32 sums before LayerNorm; the few-token GEMM may leave several partial sums
+        size_t rows = (size_t)T;
+        if (prec != STI_PREC_F32 && T <= kSkinnyMaxTokens) rows *= kSkinnyMaxSplits;
+        L.pre = take(rows * dm * 4);
+    }
     L.h = take((size_t)T * dm * es);
     L.u = take((size_t)T * M * f * es);
     L.total = off;
@@ -278,6 +282,7 @@ sti_status run_layer(const sti_dims &d, const sti_shard *shards, const sti_layer
     // MFMA path: with many row tiles per weight it is cheaper to decompress the layer
     // once into a binary16 working buffer than to decode inside every row tile
     const bool predecode = !f32 && m > 0 && T >= kWorkingBufferMinTokens;
+    static_assert(kWorkingBufferMinTokens > kSkinnyMaxTokens, "the few-token GEMM decodes in registers");
     if (predecode) {
         InlineShardTable t;
         memset(&t, 0, sizeof(t));
@@ -320,19 +325,26 @@ sti_status run_layer(const sti_dims &d, const sti_shard *shards, const sti_layer
     void *qkv = ws + wl.qkv, *ctx = ws + wl.ctx, *h = ws + wl.h, *u = ws + wl.u;
     float *pre = (float *)(ws + wl.pre);
     const sti_dtype act_dtype = f32 ? STI_F32 : STI_F16;
+    const bool skinny = !f32 && T <= kSkinnyMaxTokens;
+    const int64_t partial_stride = (int64_t)T * dm;
+    int pre_partials = 1;   // partial sums the last K-split GEMM left in `pre`
     auto gemm = [&](const GemmProblem &p, const GemmBlocks &blk) {
         static const int cls[4] = {STI_K_GEMM_QKV, STI_K_GEMM_FFN_UP, STI_K_GEMM_OUT,
                                    STI_K_GEMM_FFN_DOWN};
         return timed(cls[p.kind], stream, [&] {
-            return f32 ? launch_gemm_f32(p, blk, stream) : launch_gemm_mfma(p, blk, stream);
+            if (f32) return launch_gemm_f32(p, blk, stream);
+            if (!skinny) return launch_gemm_mfma(p, blk, stream);
+            const int splits = skinny_k_splits(p);
+            if (p.kind == GEMM_OUT || p.kind == GEMM_FFN_DOWN) pre_partials = splits;
+            return launch_gemm_skinny(p, blk, splits, partial_stride, stream);
         });
     };
     // the MFMA GEMMs leave bias and residual to the LayerNorm kernel
     auto layernorm = [&](void *dst, sti_dtype dt, const float *g, const float *b,
                          const float *bias, const void *resid) {
         return timed(STI_K_LAYERNORM, stream, [&] {
-            return launch_layernorm(pre, f32 ? nullptr : bias, f32 ? nullptr : resid, dst, dt, g, b,
-                                    T, dm, d.ln_eps, stream);
+            return launch_layernorm(pre, pre_partials, partial_stride, f32 ? nullptr : bias,
+                                    f32 ? nullptr : resid, dst, dt, g, b, T, dm, d.ln_eps, stream);
         });
     };
 

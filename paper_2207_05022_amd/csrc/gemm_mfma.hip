@@ -228,6 +228,8 @@ __global__ __launch_bounds__(256, (RA * RB >= 4 ? 2 : 3)) void gemm_mfma_kernel(
         }
     }
     __syncthreads();   // every wave is done with the A tiles; reuse them as output staging
+    // each wave stages through a region of its own; LDS serves one wave's requests in order,
+    // so no barrier is needed between its writes and its reads
     _Float16 *stage = &sm.a[0][0][0] + wave * (32 * LDC);
     _Float16 *C = (_Float16 *)p.C;
 #pragma unroll
@@ -240,16 +242,25 @@ __global__ __launch_bounds__(256, (RA * RB >= 4 ? 2 : 3)) void gemm_mfma_kernel(
                 if (p.kind == GEMM_FFN_UP) x = gelu_fast(x);
                 stage[((v >> 2) * 8 + g * 4 + (v & 3)) * LDC + r * 32 + lr] = (_Float16)x;
             }
-        __syncthreads();
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        u32x4 chunk[2 * RB];
 #pragma unroll
         for (int j = 0; j < 2 * RB; ++j) {
             const int c = lane + 64 * j;              // 16-byte chunk of the 32 x (RB*32) tile
+            chunk[j] = *(const u32x4 *)(stage + (c / (RB * 4)) * LDC + (c % (RB * 4)) * 8);
+        }
+#pragma unroll
+        for (int j = 0; j < 2 * RB; ++j) {
+            const int c = lane + 64 * j;
             const int row = c / (RB * 4), cc = c % (RB * 4);
             const int m = m0 + mw + i * 32 + row;
-            if (wave_active && m < p.T)
-                *(u32x4 *)(C + (int64_t)m * p.ldc + nw + cc * 8) = *(const u32x4 *)(stage + row * LDC + cc * 8);
+            if (wave_active && m < p.T) *(u32x4 *)(C + (int64_t)m * p.ldc + nw + cc * 8) = chunk[j];
         }
-        __syncthreads();
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     }
 }
 

@@ -1,0 +1,246 @@
+// Projections for few tokens (T <= 256): the regime of single-sequence inference, where
+// every weight is used once and the layer is bound by how fast the packed shards stream in
+// (Section "Submodel execution" runs one input at a time).
+//
+// A workgroup owns one 32-column strip of the output and a range of the K dimension; its
+// four waves take interleaved 64-wide K tiles of that range (split-K inside the workgroup),
+// decode their weights in registers with the shared per-lane loader, read their A fragments
+// straight from global memory (A is a few hundred KiB and cache resident), and reduce the
+// four partial accumulators through LDS.  Long reductions (FFN2) are additionally split
+// across workgroups; those write float32 partial sums that the LayerNorm kernel adds up in
+// a fixed order, so results do not depend on scheduling.
+#include "sti_internal.hpp"
+#include "weight_loader.hpp"
+
+namespace sti {
+namespace {
+
+constexpr int BK = 64;
+
+__device__ inline float gelu_fast(float z)
+{
+    // erf by Abramowitz & Stegun 7.1.26 (|error| < 1.5e-7); results are rounded to binary16
+    const float x = fabsf(z) * 0.70710678118654752440f;
+    const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, x, 1.0f));
+    float poly = fmaf(1.061405429f, t, -1.453152027f);
+    poly = fmaf(poly, t, 1.421413741f);
+    poly = fmaf(poly, t, -0.284496736f);
+    poly = fmaf(poly, t, 0.254829592f);
+    const float e = __builtin_amdgcn_exp2f(-x * x * 1.44269504088896340736f);
+    const float erf_abs = 1.0f - poly * t * e;
+    return 0.5f * z * (1.0f + (z < 0.f ? -erf_abs : erf_abs));
+}
+
+template <int RA>
+struct SkinnySmem {
+    float red[4][RA][16][64];                        // partial accumulators of the four waves
+    uint16_t lut[kMaxShardsPerLayer][kLutEntries];   // codebooks as binary16
+    _Float16 stage[4][32][40];                       // output staging, one 32 x 32 tile per wave
+};
+
+// grid: x = 32-column strip, y = K split, z = 128-row block of A
+template <int RA>
+__global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmProblem p, GemmBlocks blocks,
+                                                          int k_splits, int64_t partial_stride)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+    SkinnySmem<RA> &sm = *reinterpret_cast<SkinnySmem<RA> *>(smem_raw);
+    const bool n_split = (p.kind == GEMM_QKV || p.kind == GEMM_FFN_UP);
+    const int K = n_split ? p.block_cols : p.n_blocks * p.block_cols;
+    const int nkt = K / BK;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int g = lane >> 5, lr = lane & 31;
+    const int nw = blockIdx.x * 32;             // first output column of the strip
+    const int m0 = blockIdx.z * 128;            // first token row of this block
+    const int split = blockIdx.y;
+    const int kt_begin = (int)((int64_t)nkt * split / k_splits);
+    const int kt_end = (int)((int64_t)nkt * (split + 1) / k_splits);
+
+    for (int i = tid; i < p.n_blocks * kLutEntries; i += 256) {
+        const int b = i / kLutEntries, e = i % kLutEntries;
+        const int bits = blocks.b[b].bits;
+        if (bits <= 6 && e < (1 << bits)) sm.lut[b][e] = (uint16_t)f16_bits(blocks.b[b].codebook[e]);
+    }
+
+    int nblk = 0, nrow0 = nw;
+    if (n_split) {
+        nblk = nw / p.block_rows;
+        nrow0 = nw - nblk * p.block_rows;
+    }
+    const int tiles_per_kblock = n_split ? nkt : p.block_cols / BK;
+
+    struct BStage {
+        Raw raw;
+        int bits, blk;
+    };
+    auto fetch_b = [&](int kt) -> BStage {
+        BStage st;
+        int blk, ktb, row;
+        if (n_split) {
+            blk = nblk; ktb = kt; row = nrow0;
+        } else {
+            blk = kt / tiles_per_kblock; ktb = kt - blk * tiles_per_kblock; row = nw;
+        }
+        const int bits = blocks.b[blk].bits;
+        st.bits = bits; st.blk = blk;
+        const uint8_t *base = (const uint8_t *)blocks.b[blk].w;
+        if (bits == kTiledBits) {
+            st.raw = load_tiled(base + tiled_cell_offset(row >> 5, ktb, p.block_cols), lane);
+        } else {
+            const int64_t elem = (int64_t)(row + lr) * p.block_cols + ktb * BK + g * 32;
+            st.raw = load_raw_any(bits, base + (elem >> 5) * (bits * 4));
+        }
+        return st;
+    };
+    struct AStage {
+        u32x4 f[RA][4];
+    };
+    const _Float16 *A = (const _Float16 *)p.A;
+    auto fetch_a = [&](int kt) -> AStage {
+        AStage st;
+#pragma unroll
+        for (int i = 0; i < RA; ++i) {
+            const int m = m0 + i * 32 + lr;
+            const _Float16 *src = A + (int64_t)m * p.lda + kt * BK + g * 32;
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                u32x4 v = {0, 0, 0, 0};
+                if (m < p.T) v = *(const u32x4 *)(src + s * 8);
+                st.f[i][s] = v;
+            }
+        }
+        return st;
+    };
+
+    float16v acc[RA];
+#pragma unroll
+    for (int i = 0; i < RA; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
+
+    int kt = kt_begin + wave;
+    AStage a_cur;
+    BStage b_cur;
+    if (kt < kt_end) { b_cur = fetch_b(kt); a_cur = fetch_a(kt); }
+    __syncthreads();   // codebooks visible
+    for (; kt < kt_end; kt += 4) {
+        const BStage bs = b_cur;
+        const AStage as = a_cur;
+        if (kt + 4 < kt_end) { b_cur = fetch_b(kt + 4); a_cur = fetch_a(kt + 4); }
+        half8 bf[4];
+        decode_raw_any(bs.bits, bs.raw, sm.lut[bs.blk], bf);
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+#pragma unroll
+            for (int i = 0; i < RA; ++i)
+                acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8, as.f[i][s]),
+                                                               bf[s], acc[i], 0, 0, 0);
+    }
+
+    // ---- reduce the four partial accumulators; wave w finishes fragment(s) i == w (mod 4) ----
+#pragma unroll
+    for (int i = 0; i < RA; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) sm.red[wave][i][v][lane] = acc[i][v];
+    __syncthreads();
+
+    float bias = 0.f;
+    if (n_split) {
+        const int nrow = nrow0 + lr;
+        if (p.kind == GEMM_QKV) {
+            const int which = nrow / p.d_head, e = nrow - which * p.d_head;
+            const float *bp = which == 0 ? p.bias0 : (which == 1 ? p.bias1 : p.bias2);
+            bias = bp[blocks.b[nblk].shard * p.d_head + e];
+        } else {
+            bias = p.bias0[blocks.b[nblk].shard * p.block_rows + nrow];
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < RA; ++i) {
+        if ((i & 3) != wave) continue;   // wave-uniform
+        float sum[16];
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+            sum[v] = (sm.red[0][i][v][lane] + sm.red[1][i][v][lane]) +
+                     (sm.red[2][i][v][lane] + sm.red[3][i][v][lane]);
+        if (!n_split) {
+            // raw float32 (partial) sums; bias, residual and LayerNorm follow in the row kernel
+            float *C = (float *)p.C + (int64_t)split * partial_stride;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int m = m0 + i * 32 + (v >> 2) * 8 + g * 4 + (v & 3);
+                if (m < p.T) C[(int64_t)m * p.ldc + nw + lr] = sum[v];
+            }
+        } else {
+            _Float16 *st = &sm.stage[wave][0][0];
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                float x = sum[v] + bias;
+                if (p.kind == GEMM_FFN_UP) x = gelu_fast(x);
+                st[((v >> 2) * 8 + g * 4 + (v & 3)) * 40 + lr] = (_Float16)x;
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            _Float16 *C = (_Float16 *)p.C;
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const int c = lane + 64 * j;   // 16-byte chunk of the 32 x 32 tile
+                const int row = c >> 2, cc = c & 3;
+                const int m = m0 + i * 32 + row;
+                if (m < p.T)
+                    *(u32x4 *)(C + (int64_t)m * p.ldc + nw + cc * 8) = *(const u32x4 *)(st + row * 40 + cc * 8);
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        }
+    }
+}
+
+template <int RA>
+hipError_t launch_ra(const GemmProblem &p, const GemmBlocks &blocks, int N, int k_splits,
+                     int64_t partial_stride, hipStream_t stream)
+{
+    dim3 grid(N / 32, k_splits, (p.T + 127) / 128);
+    static bool attr_set = false;   // more than 64 KiB of dynamic LDS needs an explicit opt-in
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void *)gemm_skinny_kernel<RA>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           (int)sizeof(SkinnySmem<RA>));
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    gemm_skinny_kernel<RA><<<grid, dim3(256), sizeof(SkinnySmem<RA>), stream>>>(p, blocks, k_splits,
+                                                                              partial_stride);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+int skinny_k_splits(const GemmProblem &p)
+{
+    const bool n_split = (p.kind == GEMM_QKV || p.kind == GEMM_FFN_UP);
+    if (n_split) return 1;
+    const int nkt = p.n_blocks * p.block_cols / BK;
+    int s = nkt / 16;             // keep about four K tiles per wave
+    if (s < 1) s = 1;
+    if (s > kSkinnyMaxSplits) s = kSkinnyMaxSplits;
+    return s;
+}
+
+hipError_t launch_gemm_skinny(const GemmProblem &p, const GemmBlocks &blocks, int k_splits,
+                              int64_t partial_stride, hipStream_t stream)
+{
+    const bool n_split = (p.kind == GEMM_QKV || p.kind == GEMM_FFN_UP);
+    const int N = n_split ? p.n_blocks * p.block_rows : p.block_rows;
+    if (p.T <= 0 || N <= 0) return hipSuccess;
+    if (N % 32 || p.block_rows % 32 || p.block_cols % BK || p.lda % 8 || p.ldc % 8 || k_splits < 1)
+        return hipErrorInvalidValue;
+    if (p.T <= 32) return launch_ra<1>(p, blocks, N, k_splits, partial_stride, stream);
+    if (p.T <= 64) return launch_ra<2>(p, blocks, N, k_splits, partial_stride, stream);
+    return launch_ra<4>(p, blocks, N, k_splits, partial_stride, stream);
+}
+
+}  // namespace sti

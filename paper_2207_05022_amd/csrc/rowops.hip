@@ -44,7 +44,8 @@ template <> struct Elem<STI_BF16> {
 // v[t][:] = pre[t][:] (+ bias[:]) (+ resid[t][:]);  y[t][:] = LayerNorm(v) * g + b.
 // One wave per row; two-pass mean / variance in float32.  General sizes.
 template <int DT>
-__global__ __launch_bounds__(256) void layernorm_kernel(const float *pre, const float *bias,
+__global__ __launch_bounds__(256) void layernorm_kernel(const float *pre, int n_partials,
+                                                        int64_t partial_stride, const float *bias,
                                                         const _Float16 *resid,
                                                         typename Elem<DT>::type *y, const float *g,
                                                         const float *b, int T, int d, float eps)
@@ -56,6 +57,7 @@ __global__ __launch_bounds__(256) void layernorm_kernel(const float *pre, const 
     const _Float16 *rs = resid ? resid + (int64_t)row * d : nullptr;
     auto value = [&](int c) {
         float v = r[c];
+        for (int s = 1; s < n_partials; ++s) v += r[(int64_t)s * partial_stride + c];
         if (bias) v += bias[c];
         if (rs) v += (float)rs[c];
         return v;
@@ -80,8 +82,9 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef _Float16 half4 __attribute__((ext_vector_type(4)));
 
 template <int DT>
-__global__ __launch_bounds__(256) void layernorm_vec_kernel(const float *pre, const float *bias,
-                                                            const _Float16 *resid,
+__global__ __launch_bounds__(256) void layernorm_vec_kernel(const float *pre, int n_partials,
+                                                            int64_t partial_stride,
+                                                            const float *bias, const _Float16 *resid,
                                                             typename Elem<DT>::type *y,
                                                             const float *g, const float *b, int T,
                                                             int d, float eps)
@@ -100,6 +103,8 @@ __global__ __launch_bounds__(256) void layernorm_vec_kernel(const float *pre, co
         v[j] = f32x4{0.f, 0.f, 0.f, 0.f};
         if (c < nchunk) {
             f32x4 x = r[c];
+            for (int s = 1; s < n_partials; ++s)
+                x += *(const f32x4 *)(pre + (int64_t)s * partial_stride + (int64_t)row * d + 4 * c);
             if (bias) x += ((const f32x4 *)bias)[c];
             if (resid) {
                 half4 h = ((const half4 *)(resid + (int64_t)row * d))[c];
@@ -170,29 +175,32 @@ hipError_t convert_from(const void *src, void *dst, sti_dtype dst_dtype, uint64_
 }  // namespace
 
 template <int DT>
-void launch_ln_typed(const float *pre, const float *bias, const void *resid, void *y, const float *g,
-                     const float *b, int T, int d, float eps, bool vec, hipStream_t stream)
+void launch_ln_typed(const float *pre, int n_partials, int64_t partial_stride, const float *bias,
+                     const void *resid, void *y, const float *g, const float *b, int T, int d, float eps,
+                     bool vec, hipStream_t stream)
 {
     typedef typename Elem<DT>::type O;
     dim3 grid((T + 3) / 4);
     if (vec)
-        layernorm_vec_kernel<DT><<<grid, 256, 0, stream>>>(pre, bias, (const _Float16 *)resid, (O *)y, g, b, T, d, eps);
+        layernorm_vec_kernel<DT><<<grid, 256, 0, stream>>>(pre, n_partials, partial_stride, bias, (const _Float16 *)resid, (O *)y, g, b, T, d, eps);
     else
-        layernorm_kernel<DT><<<grid, 256, 0, stream>>>(pre, bias, (const _Float16 *)resid, (O *)y, g, b, T, d, eps);
+        layernorm_kernel<DT><<<grid, 256, 0, stream>>>(pre, n_partials, partial_stride, bias, (const _Float16 *)resid, (O *)y, g, b, T, d, eps);
 }
 
-hipError_t launch_layernorm(const float *pre, const float *bias, const void *resid_f16, void *y,
-                            sti_dtype out_dtype, const float *g, const float *b, int T, int d,
-                            float eps, hipStream_t stream)
+hipError_t launch_layernorm(const float *pre, int n_partials, int64_t partial_stride,
+                            const float *bias, const void *resid_f16, void *y, sti_dtype out_dtype,
+                            const float *g, const float *b, int T, int d, float eps,
+                            hipStream_t stream)
 {
     if (T <= 0 || d <= 0) return hipSuccess;
+    if (n_partials < 1) return hipErrorInvalidValue;
     auto al16 = [](const void *p) { return ((uintptr_t)p & 15) == 0; };
-    const bool vec = d % 4 == 0 && d <= 2048 && al16(pre) && al16(g) && al16(b) && al16(y) &&
+    const bool vec = d % 4 == 0 && d <= 2048 && partial_stride % 4 == 0 && al16(pre) && al16(g) && al16(b) && al16(y) &&
                      (!bias || al16(bias)) && (!resid_f16 || al16(resid_f16));
     switch (out_dtype) {
-        case STI_F32: launch_ln_typed<STI_F32>(pre, bias, resid_f16, y, g, b, T, d, eps, vec, stream); break;
-        case STI_F16: launch_ln_typed<STI_F16>(pre, bias, resid_f16, y, g, b, T, d, eps, vec, stream); break;
-        case STI_BF16: launch_ln_typed<STI_BF16>(pre, bias, resid_f16, y, g, b, T, d, eps, vec, stream); break;
+        case STI_F32: launch_ln_typed<STI_F32>(pre, n_partials, partial_stride, bias, resid_f16, y, g, b, T, d, eps, vec, stream); break;
+        case STI_F16: launch_ln_typed<STI_F16>(pre, n_partials, partial_stride, bias, resid_f16, y, g, b, T, d, eps, vec, stream); break;
+        case STI_BF16: launch_ln_typed<STI_BF16>(pre, n_partials, partial_stride, bias, resid_f16, y, g, b, T, d, eps, vec, stream); break;
     }
     return hipGetLastError();
 }

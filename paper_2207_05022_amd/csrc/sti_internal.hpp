@@ -83,12 +83,23 @@ hipError_t launch_gemm_mfma(const GemmProblem &p, const GemmBlocks &blocks, hipS
 hipError_t launch_attention_mfma(const void *qkv, void *ctx, int B, int L, int m, int dh,
                                  hipStream_t stream);
 
+// Few-token variant of the MFMA GEMM (gemm_skinny.hip): T <= 256, split-K inside the
+// workgroup and, for the K-split kinds, across `k_splits` workgroups that write float32
+// partial sums at C + s * partial_stride (to be added by launch_layernorm).
+constexpr int kSkinnyMaxTokens = 256;
+constexpr int kSkinnyMaxSplits = 8;
+int skinny_k_splits(const GemmProblem &p);
+hipError_t launch_gemm_skinny(const GemmProblem &p, const GemmBlocks &blocks, int k_splits,
+                              int64_t partial_stride, hipStream_t stream);
+
 // rowops.hip
-// y[t][:] = LayerNorm(pre[t][:] + bias[:] + resid[t][:]) * g + b; pre float32 [T x d];
-// bias (float32 [d]) and resid_f16 (binary16 [T x d]) may be NULL; y of out_dtype.
-hipError_t launch_layernorm(const float *pre, const float *bias, const void *resid_f16, void *y,
-                            sti_dtype out_dtype, const float *g, const float *b, int T, int d,
-                            float eps, hipStream_t stream);
+// v = sum_{s < n_partials} pre[s * partial_stride + t*d + :] + bias[:] + resid[t][:];
+// y[t][:] = LayerNorm(v) * g + b.  pre float32; bias (float32 [d]) and resid_f16 (binary16
+// [T x d]) may be NULL; y of out_dtype.
+hipError_t launch_layernorm(const float *pre, int n_partials, int64_t partial_stride,
+                            const float *bias, const void *resid_f16, void *y, sti_dtype out_dtype,
+                            const float *g, const float *b, int T, int d, float eps,
+                            hipStream_t stream);
 // elementwise conversion between activation types
 hipError_t launch_convert(const void *src, sti_dtype src_dtype, void *dst, sti_dtype dst_dtype,
                           uint64_t n, hipStream_t stream);
