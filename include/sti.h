@@ -93,9 +93,9 @@ typedef struct {
     int8_t bitwidth;             /* 0 = absent, 2..6 = packed indexes, 32 = raw float32          */
     const void *data;            /* DEVICE. ceil(n*k/8) bytes or n float32; 16-byte aligned      */
     const float *codebook;       /* DEVICE. 2^k float32 centroids, 4-byte aligned; ignored for 32 */
-    uint32_t n_outliers;         /* reserved for the outlier dictionary; must be 0               */
-    const uint32_t *outlier_pos; /* reserved; must be NULL                                       */
-    const float *outlier_val;    /* reserved; must be NULL                                       */
+    uint32_t n_outliers;         /* entries of the outlier dictionary (0 = none; must be 0 for 32) */
+    const uint32_t *outlier_pos; /* DEVICE. distinct offsets (< n) of the outliers inside the shard */
+    const float *outlier_val;    /* DEVICE. their original float32 weights                         */
 } sti_shard;
 
 /* Resident full-precision parameters of one layer.  All DEVICE float32. */
@@ -118,7 +118,12 @@ const char *sti_status_string(sti_status s);
  *
  * For s in [0, n_shards), j in [0, weights_per_shard):
  *     out[s*weights_per_shard + j] = round_to(out_dtype, codebook_s[index_s[j]])
- * or the raw value for a 32-bit shard.  Rounding to F16/BF16 is to nearest,
+ * or the raw value for a 32-bit shard; then, for every entry t of the shard's
+ * outlier dictionary (Section "Implementation": outliers keep a k-bit
+ * placeholder; their original weights and offsets are bookkept),
+ *     out[s*weights_per_shard + outlier_pos[t]] = round_to(out_dtype, outlier_val[t]).
+ * Offsets must be distinct; offsets >= weights_per_shard are ignored.  The layer
+ * entry points apply the same dictionary.  Rounding to F16/BF16 is to nearest,
  * ties to even, subnormals kept, overflow to infinity; F32 output is the
  * centroid bit for bit.
  *
@@ -129,8 +134,8 @@ const char *sti_status_string(sti_status s);
  *                    bytes, 16-byte aligned; may be NULL when that size is 0.
  *
  * Errors: NULL / DIMS (negative counts) / BITWIDTH / MISSING_SHARD (data NULL,
- * or codebook NULL for k <= 6) / ALIGN / WORKSPACE / DTYPE / UNSUPPORTED
- * (n_outliers != 0) / HIP.
+ * or codebook NULL for k <= 6) / NULL (outlier arrays missing) / ALIGN /
+ * WORKSPACE / DTYPE / UNSUPPORTED (outliers on a 32-bit shard) / HIP.
  * ------------------------------------------------------------------------- */
 size_t sti_decode_workspace_bytes(int n_shards);
 

@@ -17,7 +17,8 @@ F32, F16, BF16 = 0, 1, 2
 
 
 class _Shard(C.Structure):
-    _fields_ = [("bitwidth", C.c_int32), ("data", C.c_void_p), ("codebook", C.c_void_p)]
+    _fields_ = [("bitwidth", C.c_int32), ("data", C.c_void_p), ("codebook", C.c_void_p),
+                ("n_outliers", C.c_uint32), ("outlier_pos", C.c_void_p), ("outlier_val", C.c_void_p)]
 
 
 class _Params(C.Structure):
@@ -86,6 +87,16 @@ def _shard_array(shards: Sequence, keep: list):
         arr[i].bitwidth = int(s.bitwidth)
         arr[i].data = data.ctypes.data
         arr[i].codebook = cb.ctypes.data if cb is not None else None
+        pos = getattr(s, "outlier_pos", None)
+        if pos is not None and len(pos):
+            pos = np.ascontiguousarray(pos, dtype=np.uint32)
+            val = np.ascontiguousarray(s.outlier_val, dtype=np.float32)
+            if pos.size != val.size:
+                raise ValueError("outlier_pos and outlier_val differ in length")
+            keep += [pos, val]
+            arr[i].n_outliers = pos.size
+            arr[i].outlier_pos = pos.ctypes.data
+            arr[i].outlier_val = val.ctypes.data
     return arr
 
 

@@ -15,7 +15,8 @@
  * Decode (Section "quantization per shard", "storing shards per version"):
  *   a k-bit shard is a gap-free bitstream of k-bit dictionary indexes, least
  *   significant bit first, plus 2^k float32 centroids; decompression
- *   substitutes each index by its centroid.  A 32-bit shard is raw float32.
+ *   substitutes each index by its centroid, then puts the bookkept outliers
+ *   back at their offsets.  A 32-bit shard is raw float32.
  * Shard layout (Table 1): six row-major [out][in] sub-blocks
  *   Wq[dh x d] Wk[dh x d] Wv[dh x d] Wo[d x dh] W1[f x d] W2[d x f].
  * Layer (Section "A primer on transformer", "vertical partitioning"):
@@ -43,9 +44,12 @@
 
 /* One fidelity version of one shard; all pointers are host pointers. */
 typedef struct {
-    int32_t bitwidth;       /* 0 absent, 2..6 packed indexes, 32 raw float32 */
-    const void *data;       /* ceil(n*k/8) bytes, or n float32               */
-    const float *codebook;  /* 2^k float32 centroids; unused for 32          */
+    int32_t bitwidth;            /* 0 absent, 2..6 packed indexes, 32 raw float32        */
+    const void *data;            /* ceil(n*k/8) bytes, or n float32                       */
+    const float *codebook;       /* 2^k float32 centroids; unused for 32                  */
+    uint32_t n_outliers;         /* outlier dictionary (Section "Implementation": outliers */
+    const uint32_t *outlier_pos; /*   keep a k-bit placeholder; their original weights and */
+    const float *outlier_val;    /*   offsets in the shard are bookkept); distinct offsets */
 } oracle_shard;
 
 /* Resident full-fidelity parameters of one layer (Section "Implementation",
@@ -150,6 +154,11 @@ int oracle_decode_f32(const oracle_shard *sh, uint64_t n, float *out)
 #pragma omp parallel for schedule(static)
     for (int64_t j = 0; j < (int64_t)n; ++j)
         out[j] = cb[oracle_unpack_index(s, k, (uint64_t)j)];
+    for (uint32_t t = 0; t < sh->n_outliers; ++t) {
+        if (!sh->outlier_pos || !sh->outlier_val) return ORACLE_ERR_ARG;
+        if (sh->outlier_pos[t] >= n) return ORACLE_ERR_ARG;
+        out[sh->outlier_pos[t]] = sh->outlier_val[t];
+    }
     return ORACLE_OK;
 }
 
@@ -159,26 +168,23 @@ int oracle_decode_shards(const oracle_shard *shards, int n_shards, uint64_t n, v
 {
     if (!shards || !out || n_shards < 0) return ORACLE_ERR_ARG;
     if (dtype != ORACLE_F32 && dtype != ORACLE_F16 && dtype != ORACLE_BF16) return ORACLE_ERR_ARG;
+    float *tmp = (float *)malloc((n ? n : 1) * sizeof(float));
+    if (!tmp) return ORACLE_ERR_MEM;
     for (int s = 0; s < n_shards; ++s) {
-        const oracle_shard *sh = &shards[s];
-        int k = sh->bitwidth;
-        if (!sh->data) return ORACLE_ERR_ARG;
-        if (k != 32 && (k < 2 || k > 6 || !sh->codebook)) return ORACLE_ERR_ARG;
-        const uint8_t *st = (const uint8_t *)sh->data;
-        const float *raw = (const float *)sh->data;
-        const float *cb = sh->codebook;
+        int rc = oracle_decode_f32(&shards[s], n, tmp);   /* substitution + outliers */
+        if (rc) { free(tmp); return rc; }
 #pragma omp parallel for schedule(static)
         for (int64_t j = 0; j < (int64_t)n; ++j) {
-            float w = (k == 32) ? raw[j] : cb[oracle_unpack_index(st, k, (uint64_t)j)];
             uint64_t o = (uint64_t)s * n + (uint64_t)j;
             if (dtype == ORACLE_F32)
-                ((float *)out)[o] = w;
+                ((float *)out)[o] = tmp[j];
             else if (dtype == ORACLE_F16)
-                ((uint16_t *)out)[o] = oracle_f32_to_f16(w);
+                ((uint16_t *)out)[o] = oracle_f32_to_f16(tmp[j]);
             else
-                ((uint16_t *)out)[o] = oracle_f32_to_bf16(w);
+                ((uint16_t *)out)[o] = oracle_f32_to_bf16(tmp[j]);
         }
     }
+    free(tmp);
     return ORACLE_OK;
 }
 

@@ -110,9 +110,12 @@ def make_dims(dims) -> StiDims:
     return StiDims(dims.d_model, dims.n_heads, dims.d_head, dims.ffn_per_shard, dims.ln_eps)
 
 
-def make_shard(bitwidth: int, data=None, codebook=None) -> StiShard:
-    """data / codebook: CUDA tensors (uint8 stream or float32 weights; float32 centroids)."""
-    return StiShard(int(bitwidth), _ptr(data), _ptr(codebook), 0, None, None)
+def make_shard(bitwidth: int, data=None, codebook=None, outlier_pos=None, outlier_val=None) -> StiShard:
+    """data / codebook: CUDA tensors (uint8 stream or float32 weights; float32 centroids);
+    outlier_pos / outlier_val: optional CUDA int32 offsets and float32 weights."""
+    n_out = 0 if outlier_pos is None else int(outlier_pos.numel())
+    return StiShard(int(bitwidth), _ptr(data), _ptr(codebook), n_out,
+                    _ptr(outlier_pos) if n_out else None, _ptr(outlier_val) if n_out else None)
 
 
 def make_params(p) -> StiLayerParams:
@@ -132,7 +135,8 @@ def _shard_array(shards: Sequence) -> "C.Array":
         elif isinstance(s, StiShard):
             arr[i] = s
         else:
-            arr[i] = make_shard(s.bitwidth, s.data, s.codebook)
+            arr[i] = make_shard(s.bitwidth, s.data, s.codebook, getattr(s, "outlier_pos", None),
+                                getattr(s, "outlier_val", None))
     return arr
 
 
@@ -182,7 +186,8 @@ def make_store(store_rows: Sequence[Sequence[dict]]) -> "C.Array":
             for v, k in enumerate(VERSION_SLOTS):
                 s = versions.get(k) if versions else None
                 idx = (l * M + i) * 6 + v
-                arr[idx] = (make_shard(k, s.data, s.codebook) if s is not None
+                arr[idx] = (make_shard(k, s.data, s.codebook, getattr(s, "outlier_pos", None),
+                                       getattr(s, "outlier_val", None)) if s is not None
                             else StiShard(k, None, None, 0, None, None))
     return arr
 

@@ -150,13 +150,20 @@ hipError_t timed(int cls, hipStream_t stream, F fn)
     return e != hipSuccess ? e : e2;
 }
 
+inline ShardDesc make_desc(const sti_shard &s, int tag)
+{
+    return ShardDesc{s.data, s.codebook, s.bitwidth, tag, s.outlier_pos, s.outlier_val, s.n_outliers, 0};
+}
+
 sti_status check_decode_shard(const sti_shard &s)
 {
     const int b = s.bitwidth;
     if (b != 32 && !valid_packed_bits(b)) return STI_ERR_BITWIDTH;
     if (!s.data) return STI_ERR_MISSING_SHARD;
     if (b != 32 && !s.codebook) return STI_ERR_MISSING_SHARD;
-    if (s.n_outliers != 0 || s.outlier_pos || s.outlier_val) return STI_ERR_UNSUPPORTED;
+    if (b == 32 && s.n_outliers != 0) return STI_ERR_UNSUPPORTED;   // raw shards have no dictionary
+    if (s.n_outliers != 0 && (!s.outlier_pos || !s.outlier_val)) return STI_ERR_NULL;
+    if (s.n_outliers != 0 && (!aligned(s.outlier_pos, 4) || !aligned(s.outlier_val, 4))) return STI_ERR_ALIGN;
     if (!aligned(s.data, 16)) return STI_ERR_ALIGN;
     if (b != 32 && !aligned(s.codebook, 4)) return STI_ERR_ALIGN;
     return STI_OK;
@@ -281,25 +288,32 @@ sti_status run_layer(const sti_dims &d, const sti_shard *shards, const sti_layer
     const bool f32 = (prec == STI_PREC_F32);
     // MFMA path: with many row tiles per weight it is cheaper to decompress the layer
     // once into a binary16 working buffer than to decode inside every row tile
-    const bool predecode = !f32 && m > 0 && T >= kWorkingBufferMinTokens;
+    uint32_t max_outliers = 0;
+    for (int p = 0; p < m; ++p)
+        if (shards[present[p]].n_outliers > max_outliers) max_outliers = shards[present[p]].n_outliers;
+    // shards with an outlier dictionary always go through the working buffer, where the
+    // outliers are scattered back after the substitution pass
+    const bool predecode = !f32 && m > 0 && (T >= kWorkingBufferMinTokens || max_outliers > 0);
     static_assert(kWorkingBufferMinTokens > kSkinnyMaxTokens, "the few-token GEMM decodes in registers");
     if (predecode) {
         InlineShardTable t;
         memset(&t, 0, sizeof(t));
         for (int p = 0; p < m; ++p) {
             const sti_shard &s = shards[present[p]];
-            t.d[p] = ShardDesc{s.data, s.codebook, s.bitwidth, present[p]};
+            t.d[p] = make_desc(s, present[p]);
         }
         STI_TRY(timed(STI_K_DECODE, stream, [&] { return launch_decode_tiled(t, m, dm, dh, f, ws + wl.w16, stream); }));
+        STI_TRY(launch_patch_outliers_tiled(t, m, max_outliers, dm, dh, f, ws + wl.w16, stream));
     }
     if (f32 && m > 0) {
         InlineShardTable t;
         memset(&t, 0, sizeof(t));
         for (int p = 0; p < m; ++p) {
             const sti_shard &s = shards[present[p]];
-            t.d[p] = ShardDesc{s.data, s.codebook, s.bitwidth, present[p]};
+            t.d[p] = make_desc(s, present[p]);
         }
         STI_TRY(timed(STI_K_DECODE, stream, [&] { return launch_decode(nullptr, &t, m, wsh, ws + wl.w32, STI_F32, stream); }));
+        STI_TRY(launch_patch_outliers(nullptr, &t, m, max_outliers, wsh, ws + wl.w32, STI_F32, stream));
     }
     for (int p = 0; p < m; ++p) {
         const sti_shard &s = shards[present[p]];
@@ -446,6 +460,9 @@ sti_status sti_decode_shards(const sti_shard *shards, int n_shards, uint64_t wei
 
     hipStream_t stream = (hipStream_t)hip_stream;
     hipError_t e;
+    uint32_t max_outliers = 0;
+    for (int s = 0; s < n_shards; ++s)
+        if (shards[s].n_outliers > max_outliers) max_outliers = shards[s].n_outliers;
     if (need) {
         std::vector<ShardDesc> table;
         try {
@@ -454,21 +471,27 @@ sti_status sti_decode_shards(const sti_shard *shards, int n_shards, uint64_t wei
             return STI_ERR_HIP;
         }
         for (int s = 0; s < n_shards; ++s)
-            table[s] = ShardDesc{shards[s].data, shards[s].codebook, shards[s].bitwidth, s};
+            table[s] = make_desc(shards[s], s);
         e = staging().upload(table.data(), table.size(), workspace, stream);
         if (e != hipSuccess) return STI_ERR_HIP;
         e = timed(STI_K_DECODE, stream, [&] {
             return launch_decode((const ShardDesc *)workspace, nullptr, n_shards, weights_per_shard,
                                  out, out_dtype, stream);
         });
+        if (e == hipSuccess)
+            e = launch_patch_outliers((const ShardDesc *)workspace, nullptr, n_shards, max_outliers,
+                                      weights_per_shard, out, out_dtype, stream);
     } else {
         InlineShardTable t;
         memset(&t, 0, sizeof(t));
         for (int s = 0; s < n_shards; ++s)
-            t.d[s] = ShardDesc{shards[s].data, shards[s].codebook, shards[s].bitwidth, s};
+            t.d[s] = make_desc(shards[s], s);
         e = timed(STI_K_DECODE, stream, [&] {
             return launch_decode(nullptr, &t, n_shards, weights_per_shard, out, out_dtype, stream);
         });
+        if (e == hipSuccess)
+            e = launch_patch_outliers(nullptr, &t, n_shards, max_outliers, weights_per_shard, out,
+                                      out_dtype, stream);
     }
     return e == hipSuccess ? STI_OK : STI_ERR_HIP;
 }

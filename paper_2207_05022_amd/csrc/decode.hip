@@ -278,6 +278,101 @@ __global__ __launch_bounds__(256) void decode_tiled_kernel(InlineShardTable tab,
 
 }  // namespace
 
+// ---------------------------------------------------------------------------
+// Outlier dictionary (Section "quantization per shard": the few weights that do not follow
+// the Gaussian are preserved as-is; Section "Implementation": they keep a k-bit placeholder
+// in the index matrix and their original weights and offsets are bookkept).  After the
+// substitution pass the original weights are scattered back.  grid = (chunks, shards).
+// ---------------------------------------------------------------------------
+namespace {
+
+template <typename Out, typename Table>
+__global__ __launch_bounds__(256) void patch_outliers_kernel(Table table, uint64_t n,
+                                                             typename Out::bits_t *out)
+{
+    const ShardDesc sd = table.get(blockIdx.y);
+    typename Out::bits_t *o = out + (uint64_t)blockIdx.y * n;
+    for (uint32_t t = blockIdx.x * 256 + threadIdx.x; t < sd.n_outliers; t += gridDim.x * 256) {
+        const uint32_t pos = sd.outlier_pos[t];
+        if (pos < n) o[pos] = Out::cvt(sd.outlier_val[t]);
+    }
+}
+
+template <typename Out>
+hipError_t patch_typed(const ShardDesc *table, const InlineShardTable *inline_table, int n_shards,
+                       uint32_t max_outliers, uint64_t n, void *out, hipStream_t stream)
+{
+    uint32_t chunks = (max_outliers + 255) / 256;
+    if (chunks > 1024) chunks = 1024;
+    dim3 grid(chunks, n_shards);
+    typedef typename Out::bits_t bits_t;
+    if (table) {
+        TablePtr t{table};
+        patch_outliers_kernel<Out, TablePtr><<<grid, 256, 0, stream>>>(t, n, (bits_t *)out);
+    } else {
+        TableInline t;
+        t.t = *inline_table;
+        patch_outliers_kernel<Out, TableInline><<<grid, 256, 0, stream>>>(t, n, (bits_t *)out);
+    }
+    return hipGetLastError();
+}
+
+// offset inside a shard -> byte offset inside its fragment-tiled image
+__device__ inline int64_t tiled_byte_offset(uint32_t pos, int d, int dh, int f)
+{
+    const int64_t o_o = (int64_t)3 * dh * d, o_1 = (int64_t)4 * dh * d, o_2 = o_1 + (int64_t)f * d;
+    int64_t sub_off;
+    int cols;
+    if (pos < o_o) { sub_off = 0; cols = d; }
+    else if (pos < o_1) { sub_off = o_o; cols = dh; }
+    else if (pos < o_2) { sub_off = o_1; cols = d; }
+    else { sub_off = o_2; cols = f; }
+    const int64_t rel = pos - sub_off;
+    const int row = (int)(rel / cols), col = (int)(rel - (int64_t)row * cols);
+    const int lane = ((col & 63) >> 5) * 32 + (row & 31), q = (col & 31) >> 3, e = col & 7;
+    return sub_off * 2 + tiled_cell_offset(row >> 5, col >> 6, cols) + q * 1024 + lane * 16 + e * 2;
+}
+
+__global__ __launch_bounds__(256) void patch_outliers_tiled_kernel(InlineShardTable tab, int d,
+                                                                   int dh, int f, uint8_t *out)
+{
+    const ShardDesc sd = tab.d[blockIdx.y];
+    const int64_t wsh = (int64_t)d * (4 * dh + 2 * f);
+    uint8_t *o = out + (int64_t)blockIdx.y * wsh * 2;
+    for (uint32_t t = blockIdx.x * 256 + threadIdx.x; t < sd.n_outliers; t += gridDim.x * 256) {
+        const uint32_t pos = sd.outlier_pos[t];
+        if (pos < wsh) *(uint16_t *)(o + tiled_byte_offset(pos, d, dh, f)) = to_f16_bits(sd.outlier_val[t]);
+    }
+}
+
+}  // namespace
+
+hipError_t launch_patch_outliers(const ShardDesc *table, const InlineShardTable *inline_table,
+                                 int n_shards, uint32_t max_outliers, uint64_t n, void *out,
+                                 sti_dtype out_dtype, hipStream_t stream)
+{
+    if (n_shards <= 0 || max_outliers == 0 || n == 0) return hipSuccess;
+    if (n_shards > 65535) return hipErrorInvalidValue;
+    switch (out_dtype) {
+        case STI_F32: return patch_typed<OutF32>(table, inline_table, n_shards, max_outliers, n, out, stream);
+        case STI_F16: return patch_typed<OutF16>(table, inline_table, n_shards, max_outliers, n, out, stream);
+        case STI_BF16: return patch_typed<OutBF16>(table, inline_table, n_shards, max_outliers, n, out, stream);
+    }
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_patch_outliers_tiled(const InlineShardTable &table, int n_shards,
+                                       uint32_t max_outliers, int d, int dh, int f, void *out,
+                                       hipStream_t stream)
+{
+    if (n_shards <= 0 || max_outliers == 0) return hipSuccess;
+    uint32_t chunks = (max_outliers + 255) / 256;
+    if (chunks > 1024) chunks = 1024;
+    patch_outliers_tiled_kernel<<<dim3(chunks, n_shards), 256, 0, stream>>>(table, d, dh, f,
+                                                                            (uint8_t *)out);
+    return hipGetLastError();
+}
+
 hipError_t launch_decode_tiled(const InlineShardTable &table, int n_shards, int d, int dh, int f,
                                void *out, hipStream_t stream)
 {

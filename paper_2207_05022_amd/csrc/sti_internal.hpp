@@ -15,6 +15,10 @@ struct ShardDesc {
     const float *codebook;  // 2^bits centroids (unused for 32)
     int32_t bits;           // 2..6 or 32
     int32_t tag;            // original shard id inside its layer
+    const uint32_t *outlier_pos;   // distinct offsets of the outlier dictionary
+    const float *outlier_val;      // their original float32 weights
+    uint32_t n_outliers;
+    uint32_t pad;
 };
 
 struct InlineShardTable {
@@ -26,6 +30,16 @@ struct InlineShardTable {
 // device pointer to n_shards descriptors, or NULL to use `inline_table`.
 hipError_t launch_decode(const ShardDesc *table, const InlineShardTable *inline_table, int n_shards,
                          uint64_t n, void *out, sti_dtype out_dtype, hipStream_t stream);
+
+// Put the bookkept outliers back: out[s*n + pos] = round_to(out_dtype, val) for every entry of
+// every shard's outlier dictionary (offsets >= n are ignored).  Runs after launch_decode.
+hipError_t launch_patch_outliers(const ShardDesc *table, const InlineShardTable *inline_table,
+                                 int n_shards, uint32_t max_outliers, uint64_t n, void *out,
+                                 sti_dtype out_dtype, hipStream_t stream);
+// Same for the fragment-tiled binary16 working buffer written by launch_decode_tiled.
+hipError_t launch_patch_outliers_tiled(const InlineShardTable &table, int n_shards,
+                                       uint32_t max_outliers, int d, int dh, int f, void *out,
+                                       hipStream_t stream);
 
 // Decode n_shards shards of a layer (d, dh, f geometry) into the fragment-tiled binary16
 // working buffer out[n_shards][Wsh] used by the matrix-core GEMM (see weight_loader.hpp).

@@ -22,7 +22,12 @@ def upload_shard(sh, device="cuda"):
     else:
         data = torch.from_numpy(np.ascontiguousarray(sh.data, dtype=np.uint8)).to(device)
         cb = torch.from_numpy(np.ascontiguousarray(sh.codebook, dtype=np.float32)).to(device)
-    return SimpleNamespace(bitwidth=int(sh.bitwidth), data=data, codebook=cb)
+    pos = val = None
+    if getattr(sh, "outlier_pos", None) is not None and len(sh.outlier_pos):
+        pos = torch.from_numpy(np.ascontiguousarray(sh.outlier_pos, dtype=np.uint32).view(np.int32)).to(device)
+        val = torch.from_numpy(np.ascontiguousarray(sh.outlier_val, dtype=np.float32)).to(device)
+    return SimpleNamespace(bitwidth=int(sh.bitwidth), data=data, codebook=cb, outlier_pos=pos,
+                           outlier_val=val)
 
 
 def upload_params(p, device="cuda"):

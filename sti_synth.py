@@ -85,6 +85,8 @@ class Shard:
     bitwidth: int                      # 2..6 packed indices, 32 raw float32
     data: np.ndarray                   # uint8 stream (k-bit) or float32 (32-bit)
     codebook: Optional[np.ndarray]     # float32[2**k], None for 32-bit
+    outlier_pos: Optional[np.ndarray] = None   # uint32, distinct increasing offsets in the shard
+    outlier_val: Optional[np.ndarray] = None   # float32 original weights at those offsets
 
 
 @dataclass
@@ -160,6 +162,21 @@ def make_shard(rng: np.random.Generator, n_weights: int, k: int) -> Shard:
         # bits past the last index carry no information; keep them zero
         stream[-1] &= np.uint8(0xFF >> tail_bits)
     return Shard(k, stream, make_codebook(k, sigma))
+
+
+def add_outliers(rng: np.random.Generator, shard: Shard, n_weights: int, fraction: float = 0.0015) -> Shard:
+    """Give a k-bit shard an outlier dictionary: ``fraction`` of its weights (the paper reports
+    0.14-0.17 %) at distinct uniform offsets, with magnitudes beyond the codebook's range
+    (3 to 6 times 0.02, random sign).  The k-bit placeholders in the stream stay as drawn."""
+    if shard.bitwidth == 32:
+        return shard
+    count = max(1, int(round(n_weights * fraction)))
+    pos = np.sort(rng.choice(n_weights, size=count, replace=False)).astype(np.uint32)
+    mag = rng.uniform(3 * SIGMA, 6 * SIGMA, size=count)
+    sign = rng.choice(np.array([-1.0, 1.0]), size=count)
+    shard.outlier_pos = pos
+    shard.outlier_val = (mag * sign).astype(np.float32)
+    return shard
 
 
 def make_layer_params(rng: np.random.Generator, dims: Dims) -> LayerParams:

@@ -67,7 +67,9 @@ def test_decode_argument_errors(P):
     assert decode(P, [shard(P, 4)], out=FAKE + 4) == 5
     assert decode(P, [shard(P, 4)], out=None) == 1
     assert decode(P, [shard(P, 4)], dtype=5) == 7
-    assert decode(P, [shard(P, 4, nout=3)]) == 9              # outliers not implemented
+    assert decode(P, [shard(P, 4, nout=3)]) == 1              # outlier arrays missing
+    assert decode(P, [P.StiShard(32, FAKE, None, 3, FAKE, FAKE)]) == 9   # raw shards have no dictionary
+    assert decode(P, [P.StiShard(4, FAKE, FAKE, 3, FAKE + 2, FAKE)]) == 5
     assert P.lib.sti_decode_shards(None, 3, 8, FAKE, 1, None, 0, None) == 1
     assert P.lib.sti_decode_shards(None, -1, 8, FAKE, 1, None, 0, None) == 2
     assert P.lib.sti_decode_shards(None, 0, 8, FAKE, 1, None, 0, None) == 0

@@ -102,3 +102,30 @@ def test_empty_inputs(gpu):
     P.sti_decode_shards([sh], 0, out, None)
     torch.cuda.synchronize()
     assert float(out.abs().sum()) == 0.0
+
+
+@pytest.mark.parametrize("dtype", ["f16", "f32", "bf16"])
+def test_outlier_dictionary(gpu, oracle_mod, dtype):
+    n = 16384 * 2 + 8 * 11
+    rng = np.random.default_rng(91)
+    shards = []
+    for k in (2, 3, 4, 5, 6):
+        shards.append(S.add_outliers(rng, S.make_shard(rng, n, k), n, fraction=0.0015))
+    shards.append(S.make_shard(rng, n, 32))
+    shards.append(S.make_shard(rng, n, 4))          # no dictionary
+    edge = S.make_shard(rng, n, 3)
+    edge.outlier_pos = np.array([0, 7, 8, n - 1], np.uint32)
+    edge.outlier_val = np.array([1.5, -2.5, 65520.0, 1e-8], np.float32)
+    shards.append(edge)
+    got = run_decode(gpu, shards, n, dtype)
+    want = oracle_bits(oracle_mod, shards, n, dtype)
+    assert np.array_equal(got, want)
+
+
+def test_outliers_with_device_table(gpu, oracle_mod):
+    n = 4096
+    rng = np.random.default_rng(92)
+    shards = [S.add_outliers(rng, S.make_shard(rng, n, int(k)), n, 0.01)
+              for k in rng.choice([2, 3, 4, 5, 6], size=70)]
+    got = run_decode(gpu, shards, n, "f16")
+    assert np.array_equal(got, oracle_bits(oracle_mod, shards, n, "f16"))

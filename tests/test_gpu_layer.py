@@ -215,3 +215,26 @@ def test_mfma_rejects_unsupported_dims(gpu):
     with pytest.raises(P.StiError) as ei:
         P.sti_layer_forward(SMALL, shards[0], params[0], xd, y, P.STI_PREC_F16_MFMA, ws)
     assert ei.value.status == 2
+
+
+# ------------------------------------------------------------------ outlier dictionary
+
+def _with_outliers(wl, seed, fraction=0.0015):
+    rng = np.random.default_rng(seed)
+    for row in wl.shards:
+        for s in row:
+            if s is not None:
+                S.add_outliers(rng, s, wl.dims.weights_per_shard, fraction)
+    return wl
+
+
+@pytest.mark.parametrize("prec,B,L", [("f32", 2, 9), ("mfma", 1, 40), ("mfma", 5, 128)])
+def test_layers_apply_outlier_dictionaries(gpu, oracle_mod, prec, B, L):
+    wl = _with_outliers(S.small_workload(300 + L, MID, 2, B, L, n_absent=1), 5, fraction=0.05)
+    want = oracle_mod.model_forward(MID, wl.shards, wl.params, wl.x)
+    plain = [[None if s is None else S.Shard(s.bitwidth, s.data, s.codebook) for s in row]
+             for row in wl.shards]
+    without = oracle_mod.model_forward(MID, plain, wl.params, wl.x)
+    assert rel_err(without, want) > 3 * TOL[prec]     # the dictionaries matter at this tolerance
+    got = run_gpu(gpu, wl, prec)
+    assert rel_err(got, want) <= TOL[prec]

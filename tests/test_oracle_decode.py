@@ -196,3 +196,39 @@ def test_codebook_recipe():
         assert np.allclose(cb, -cb[::-1], rtol=1e-6)
         # every centroid is a normal binary16 number after rounding
         assert np.all(np.abs(cb.astype(np.float16).astype(np.float32)) >= 6.1e-5)
+
+
+# ---------------------------------------------------------------- outlier dictionary
+
+@pytest.mark.parametrize("k", [2, 4, 5])
+def test_outliers_replace_exactly_their_offsets(oracle_mod, k):
+    n = 6000
+    rng = np.random.default_rng(40 + k)
+    sh = S.add_outliers(rng, S.make_shard(rng, n, k), n, fraction=0.01)
+    assert sh.outlier_pos.size == 60 and np.all(np.diff(sh.outlier_pos.astype(np.int64)) > 0)
+    plain = S.Shard(k, sh.data, sh.codebook)
+    base = oracle_mod.decode_shards([plain], n)[0]
+    got = oracle_mod.decode_shards([sh], n)[0]
+    mask = np.zeros(n, bool); mask[sh.outlier_pos] = True
+    assert np.array_equal(got[~mask].view(np.uint32), base[~mask].view(np.uint32))
+    assert np.array_equal(got[mask].view(np.uint32), sh.outlier_val.view(np.uint32))
+    # the substituted part is still pure codebook lookup of the big-integer indexes
+    want = sh.codebook[np.array(bigint_indexes(sh.data, k, n))]
+    want[sh.outlier_pos] = sh.outlier_val
+    assert np.array_equal(got.view(np.uint32), want.view(np.uint32))
+    # outliers are outside the centroid range, as in the paper's Gaussian outlier test
+    assert np.all(np.abs(sh.outlier_val) > np.max(np.abs(sh.codebook)))
+    # rounding applies to outliers too
+    h = oracle_mod.decode_shards([sh], n, oracle_mod.F16)[0]
+    assert np.array_equal(h[mask], sh.outlier_val.astype(np.float16).view(np.uint16))
+
+
+def test_outlier_edge_positions_and_errors(oracle_mod):
+    n = 100
+    sh = S.make_shard(np.random.default_rng(1), n, 3)
+    sh.outlier_pos = np.array([0, n - 1], np.uint32); sh.outlier_val = np.array([7.0, -9.0], np.float32)
+    got = oracle_mod.decode_shards([sh], n)[0]
+    assert got[0] == 7.0 and got[-1] == -9.0
+    sh.outlier_pos = np.array([n], np.uint32); sh.outlier_val = np.array([1.0], np.float32)
+    with pytest.raises(RuntimeError):
+        oracle_mod.decode_shards([sh], n)

@@ -288,3 +288,22 @@ def test_model_with_dense_reference_two_layers(oracle_mod):
     for l in range(2):
         cur = dense_torch_layer(SMALL, wl.shards[l], wl.params[l], cur)
     assert np.max(np.abs(y - cur)) <= 1e-12 * max(1.0, np.max(np.abs(cur)))
+
+
+def test_outlier_shard_equals_patched_full_precision_shard(oracle_mod):
+    """A k-bit shard with an outlier dictionary behaves like the float32 shard holding its
+    decoded weights with the outliers written in (decode computed by test-local numpy code)."""
+    wl = _wl(seed=23, plan=np.array([[3, 6, 4]]))
+    p = random_params(np.random.default_rng(9), SMALL)
+    rng = np.random.default_rng(10)
+    shards = [S.add_outliers(rng, s, SMALL.weights_per_shard, 0.01) for s in wl.shards[0]]
+    y = oracle_mod.layer_forward(SMALL, shards, p, wl.x)
+    patched = []
+    for s in shards:
+        w = np_decode(S.Shard(s.bitwidth, s.data, s.codebook), SMALL.weights_per_shard).copy()
+        w[s.outlier_pos] = s.outlier_val
+        patched.append(S.Shard(32, w, None))
+    y2 = oracle_mod.layer_forward(SMALL, patched, p, wl.x)
+    assert np.array_equal(y, y2)
+    plain = [S.Shard(s.bitwidth, s.data, s.codebook) for s in shards]
+    assert np.max(np.abs(y - oracle_mod.layer_forward(SMALL, plain, p, wl.x))) > 1e-4
