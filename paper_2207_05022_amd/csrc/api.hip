@@ -357,6 +357,8 @@ sti_status run_layer(const sti_dims &d, const sti_shard *shards, const sti_layer
     auto layernorm = [&](void *dst, sti_dtype dt, const float *g, const float *b,
                          const float *bias, const void *resid) {
         return timed(STI_K_LAYERNORM, stream, [&] {
+            if (!f32 && !skinny)   // the wide MFMA GEMM already added bias and residual
+                return launch_layernorm_f16in(pre, dst, dt, g, b, T, dm, d.ln_eps, stream);
             return launch_layernorm(pre, pre_partials, partial_stride, f32 ? nullptr : bias,
                                     f32 ? nullptr : resid, dst, dt, g, b, T, dm, d.ln_eps, stream);
         });

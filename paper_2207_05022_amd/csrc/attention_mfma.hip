@@ -23,13 +23,15 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int DH = 64;
 constexpr int KPAD = DH + 8;   // padded K row (halves)
-constexpr int QB = 128;        // queries per workgroup (4 waves x 32)
 
 __device__ inline int vt_stride(int Lp) { return Lp + 8; }
 
-__global__ __launch_bounds__(256) void attention_mfma_kernel(const _Float16 *qkv, _Float16 *ctx,
-                                                             int L, int Lp, int m)
+// NW waves per workgroup, 32 queries each.
+template <int NW>
+__global__ __launch_bounds__(NW * 64) void attention_mfma_kernel(const _Float16 *qkv, _Float16 *ctx,
+                                                                 int L, int Lp, int m)
 {
+    constexpr int QB = NW * 32;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     _Float16 *Ks = (_Float16 *)smem_raw;                 // [Lp][KPAD]
     _Float16 *Vt = Ks + (size_t)Lp * KPAD;               // [DH][Lp + 8]
@@ -40,18 +42,29 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(const _Float16 *qkv
     const int64_t ld = (int64_t)m * 3 * DH;
     const _Float16 *base = qkv + (int64_t)b * L * ld + (int64_t)p * 3 * DH;
 
-    // stage K (row-major) and V (transposed) of this head; rows >= L are zero
-    for (int r = tid >> 3; r < Lp; r += 32) {
+    // stage K (row-major) of this head; rows >= L are zero
+    for (int r = tid >> 3; r < Lp; r += NW * 8) {
         const int c = (tid & 7) * 8;
-        u32x4 kv = {0, 0, 0, 0}, vv = {0, 0, 0, 0};
-        if (r < L) {
-            kv = *(const u32x4 *)(base + (int64_t)r * ld + DH + c);
-            vv = *(const u32x4 *)(base + (int64_t)r * ld + 2 * DH + c);
-        }
+        u32x4 kv = {0, 0, 0, 0};
+        if (r < L) kv = *(const u32x4 *)(base + (int64_t)r * ld + DH + c);
         *(u32x4 *)(Ks + (size_t)r * KPAD + c) = kv;
-        const _Float16 *vh = (const _Float16 *)&vv;
+    }
+    // stage V transposed: a lane takes two consecutive keys and 8 features, so that the 64
+    // lanes of one LDS store write consecutive dwords of one V^T row (no bank conflicts)
+    for (int item = tid; item < (Lp / 2) * 8; item += NW * 64) {
+        const int pair = item % (Lp / 2), c = (item / (Lp / 2)) * 8;
+        const int r0 = 2 * pair;
+        u32x4 v0 = {0, 0, 0, 0}, v1 = {0, 0, 0, 0};
+        if (r0 < L) v0 = *(const u32x4 *)(base + (int64_t)r0 * ld + 2 * DH + c);
+        if (r0 + 1 < L) v1 = *(const u32x4 *)(base + (int64_t)(r0 + 1) * ld + 2 * DH + c);
+        const uint32_t a[4] = {v0.x, v0.y, v0.z, v0.w}, bq[4] = {v1.x, v1.y, v1.z, v1.w};
 #pragma unroll
-        for (int i = 0; i < 8; ++i) Vt[(size_t)(c + i) * vts + r] = vh[i];
+        for (int i = 0; i < 4; ++i) {
+            const uint32_t lo = (a[i] & 0xFFFFu) | (bq[i] << 16);          // feature c + 2i
+            const uint32_t hi = (a[i] >> 16) | (bq[i] & 0xFFFF0000u);      // feature c + 2i + 1
+            *(uint32_t *)(Vt + (size_t)(c + 2 * i) * vts + r0) = lo;
+            *(uint32_t *)(Vt + (size_t)(c + 2 * i + 1) * vts + r0) = hi;
+        }
     }
 
     // this lane's query row as the B operand of S^T = K Q^T
@@ -155,14 +168,25 @@ hipError_t launch_attention_mfma(const void *qkv, void *ctx, int B, int L, int m
     const size_t lds = ((size_t)Lp * KPAD + (size_t)DH * (Lp + 8)) * sizeof(_Float16);
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)attention_mfma_kernel,
+        hipError_t e = hipFuncSetAttribute((const void *)attention_mfma_kernel<4>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute((const void *)attention_mfma_kernel<2>,
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    dim3 grid((L + QB - 1) / QB, m, B);
-    attention_mfma_kernel<<<grid, dim3(256), lds, stream>>>((const _Float16 *)qkv, (_Float16 *)ctx,
-                                                           L, Lp, m);
+    // few (sequence, head) pairs: 64 queries per workgroup put twice as many workgroups on the chip
+    const bool small_wg = (int64_t)B * m * ((L + 127) / 128) < 128 && L > 32;
+    if (small_wg) {
+        dim3 grid((L + 63) / 64, m, B);
+        attention_mfma_kernel<2><<<grid, dim3(128), lds, stream>>>((const _Float16 *)qkv,
+                                                                   (_Float16 *)ctx, L, Lp, m);
+    } else {
+        dim3 grid((L + 127) / 128, m, B);
+        attention_mfma_kernel<4><<<grid, dim3(256), lds, stream>>>((const _Float16 *)qkv,
+                                                                   (_Float16 *)ctx, L, Lp, m);
+    }
     return hipGetLastError();
 }
 

@@ -200,18 +200,47 @@ __global__ __launch_bounds__(256, (RA * RB >= 4 ? 2 : 3)) void gemm_mfma_kernel(
 
     // ---- epilogue: lane owns column lr of each strip, rows (v/4)*8 + g*4 + v%4 of each fragment ----
     if (p.kind == GEMM_OUT || p.kind == GEMM_FFN_DOWN) {
-        // raw float32 sums; bias, residual and LayerNorm follow in the row kernel
-        if (!wave_active) return;
-        float *C = (float *)p.C;
+        // sums + bias + residual, rounded once to binary16; LayerNorm follows in the row kernel.
+        // Staged through LDS in float32 so that residual loads and stores are 16-byte row pieces.
+        constexpr int LDF = RB * 32 + 4;   // padded float32 staging row
+        static_assert(4 * 32 * LDF * 2 <= 2 * BM * LDA, "float32 staging fits in the A buffers");
+        __syncthreads();   // every wave is done with the A tiles
+        float *stage = (float *)&sm.a[0][0][0] + wave * (32 * LDF);
+        _Float16 *C = (_Float16 *)p.C;
+        const _Float16 *R = (const _Float16 *)p.resid;
 #pragma unroll
-        for (int r = 0; r < RB; ++r)
+        for (int i = 0; i < RA; ++i) {
 #pragma unroll
-            for (int i = 0; i < RA; ++i)
+            for (int r = 0; r < RB; ++r)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int m = m0 + mw + i * 32 + (v >> 2) * 8 + g * 4 + (v & 3);
-                    if (m < p.T) C[(int64_t)m * p.ldc + nw + r * 32 + lr] = acc[i][r][v];
+                for (int v = 0; v < 16; ++v)
+                    stage[((v >> 2) * 8 + g * 4 + (v & 3)) * LDF + r * 32 + lr] = acc[i][r][v];
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+            for (int j = 0; j < 2 * RB; ++j) {
+                const int c = lane + 64 * j;              // 8-column piece of the 32 x (RB*32) tile
+                const int row = c / (RB * 4), cc = c % (RB * 4);
+                const int m = m0 + mw + i * 32 + row;
+                const int n = nw + cc * 8;
+                if (wave_active && m < p.T) {
+                    const f32x4 s0 = *(const f32x4 *)(stage + row * LDF + cc * 8);
+                    const f32x4 s1 = *(const f32x4 *)(stage + row * LDF + cc * 8 + 4);
+                    const f32x4 b0 = *(const f32x4 *)(p.bias0 + n), b1 = *(const f32x4 *)(p.bias0 + n + 4);
+                    const half8 rr = *(const half8 *)(R + (int64_t)m * p.ldr + n);
+                    half8 o;
+                    o[0] = (_Float16)(s0.x + b0.x + (float)rr[0]); o[1] = (_Float16)(s0.y + b0.y + (float)rr[1]);
+                    o[2] = (_Float16)(s0.z + b0.z + (float)rr[2]); o[3] = (_Float16)(s0.w + b0.w + (float)rr[3]);
+                    o[4] = (_Float16)(s1.x + b1.x + (float)rr[4]); o[5] = (_Float16)(s1.y + b1.y + (float)rr[5]);
+                    o[6] = (_Float16)(s1.z + b1.z + (float)rr[6]); o[7] = (_Float16)(s1.w + b1.w + (float)rr[7]);
+                    *(half8 *)(C + (int64_t)m * p.ldc + n) = o;
                 }
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        }
         return;
     }
 

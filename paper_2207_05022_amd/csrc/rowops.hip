@@ -81,7 +81,17 @@ __global__ __launch_bounds__(256) void layernorm_kernel(const float *pre, int n_
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef _Float16 half4 __attribute__((ext_vector_type(4)));
 
-template <int DT>
+// LPR lanes share one row (64, 32 or 16): fewer lanes per row keep more bytes in flight per
+// lane and shorten the two reductions.
+template <int LPR>
+__device__ inline float row_sum(float v)
+{
+#pragma unroll
+    for (int o = LPR / 2; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+template <int DT, int LPR, int MAXC>   // MAXC = 16-byte chunks per lane: d <= 4 * LPR * MAXC
 __global__ __launch_bounds__(256) void layernorm_vec_kernel(const float *pre, int n_partials,
                                                             int64_t partial_stride,
                                                             const float *bias, const _Float16 *resid,
@@ -89,22 +99,22 @@ __global__ __launch_bounds__(256) void layernorm_vec_kernel(const float *pre, in
                                                             const float *g, const float *b, int T,
                                                             int d, float eps)
 {
-    constexpr int MAXC = 8;
-    const int row = blockIdx.x * 4 + threadIdx.x / 64;
-    const int lane = threadIdx.x % 64;
-    if (row >= T) return;
+    constexpr int ROWS = 256 / LPR;               // rows per workgroup
+    const int sub = threadIdx.x % LPR;
+    const int row = blockIdx.x * ROWS + threadIdx.x / LPR;
+    if (row >= T) return;   // whole row groups leave together; shuffles stay inside a group
     const int nchunk = d >> 2;
     const f32x4 *r = (const f32x4 *)(pre + (int64_t)row * d);
     f32x4 v[MAXC];
     float s = 0.f;
 #pragma unroll
     for (int j = 0; j < MAXC; ++j) {
-        const int c = lane + 64 * j;
+        const int c = sub + LPR * j;
         v[j] = f32x4{0.f, 0.f, 0.f, 0.f};
         if (c < nchunk) {
             f32x4 x = r[c];
-            for (int s = 1; s < n_partials; ++s)
-                x += *(const f32x4 *)(pre + (int64_t)s * partial_stride + (int64_t)row * d + 4 * c);
+            for (int sp = 1; sp < n_partials; ++sp)
+                x += *(const f32x4 *)(pre + (int64_t)sp * partial_stride + (int64_t)row * d + 4 * c);
             if (bias) x += ((const f32x4 *)bias)[c];
             if (resid) {
                 half4 h = ((const half4 *)(resid + (int64_t)row * d))[c];
@@ -114,21 +124,21 @@ __global__ __launch_bounds__(256) void layernorm_vec_kernel(const float *pre, in
             s += (x.x + x.y) + (x.z + x.w);
         }
     }
-    const float mean = wave_sum(s) / (float)d;
+    const float mean = row_sum<LPR>(s) / (float)d;
     float q = 0.f;
 #pragma unroll
     for (int j = 0; j < MAXC; ++j) {
-        if (lane + 64 * j < nchunk) {
+        if (sub + LPR * j < nchunk) {
             f32x4 t = v[j] - mean;
             q += (t.x * t.x + t.y * t.y) + (t.z * t.z + t.w * t.w);
         }
     }
-    const float var = wave_sum(q) / (float)d;
+    const float var = row_sum<LPR>(q) / (float)d;
     const float inv = 1.0f / sqrtf(var + eps);
     typename Elem<DT>::type *o = y + (int64_t)row * d;
 #pragma unroll
     for (int j = 0; j < MAXC; ++j) {
-        const int c = lane + 64 * j;
+        const int c = sub + LPR * j;
         if (c < nchunk) {
             const f32x4 gg = ((const f32x4 *)g)[c], bb = ((const f32x4 *)b)[c];
             const f32x4 t = (v[j] - mean) * inv * gg + bb;
@@ -139,6 +149,69 @@ __global__ __launch_bounds__(256) void layernorm_vec_kernel(const float *pre, in
             } else {
                 Elem<DT>::store(o + 4 * c, t.x); Elem<DT>::store(o + 4 * c + 1, t.y);
                 Elem<DT>::store(o + 4 * c + 2, t.z); Elem<DT>::store(o + 4 * c + 3, t.w);
+            }
+        }
+    }
+}
+
+// LayerNorm of rows that already hold sum + bias + residual in binary16 (written by the
+// matrix-core GEMM); d a multiple of 8 and at most 2048; one wave per row.
+template <int DT>
+__global__ __launch_bounds__(256) void layernorm_f16in_kernel(const _Float16 *pre,
+                                                              typename Elem<DT>::type *y,
+                                                              const float *g, const float *b, int T,
+                                                              int d, float eps)
+{
+    constexpr int MAXC = 4;   // 8-element chunks per lane
+    typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+    const int lane = threadIdx.x % 64;
+    const int row = blockIdx.x * 4 + threadIdx.x / 64;
+    if (row >= T) return;
+    const int nchunk = d >> 3;
+    const half8 *r = (const half8 *)(pre + (int64_t)row * d);
+    float v[MAXC][8];
+    float s = 0.f;
+#pragma unroll
+    for (int j = 0; j < MAXC; ++j) {
+        const int c = lane + 64 * j;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[j][e] = 0.f;
+        if (c < nchunk) {
+            const half8 h = r[c];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) { v[j][e] = (float)h[e]; s += v[j][e]; }
+        }
+    }
+    const float mean = wave_sum(s) / (float)d;
+    float q = 0.f;
+#pragma unroll
+    for (int j = 0; j < MAXC; ++j)
+        if (lane + 64 * j < nchunk) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) { const float t = v[j][e] - mean; q = fmaf(t, t, q); }
+        }
+    const float var = wave_sum(q) / (float)d;
+    const float inv = 1.0f / sqrtf(var + eps);
+    typename Elem<DT>::type *o = y + (int64_t)row * d;
+#pragma unroll
+    for (int j = 0; j < MAXC; ++j) {
+        const int c = lane + 64 * j;
+        if (c < nchunk) {
+            const f32x4 g0 = ((const f32x4 *)g)[2 * c], g1 = ((const f32x4 *)g)[2 * c + 1];
+            const f32x4 b0 = ((const f32x4 *)b)[2 * c], b1 = ((const f32x4 *)b)[2 * c + 1];
+            const float gg[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
+            const float bb[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
+            float t[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) t[e] = (v[j][e] - mean) * inv * gg[e] + bb[e];
+            if constexpr (DT == STI_F16) {
+                half8 h;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) h[e] = (_Float16)t[e];
+                ((half8 *)o)[c] = h;
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) Elem<DT>::store(o + 8 * c + e, t[e]);
             }
         }
     }
@@ -181,8 +254,11 @@ void launch_ln_typed(const float *pre, int n_partials, int64_t partial_stride, c
 {
     typedef typename Elem<DT>::type O;
     dim3 grid((T + 3) / 4);
-    if (vec)
-        layernorm_vec_kernel<DT><<<grid, 256, 0, stream>>>(pre, n_partials, partial_stride, bias, (const _Float16 *)resid, (O *)y, g, b, T, d, eps);
+    // many rows: 16 lanes per row (16 rows per workgroup); few rows: a whole wave per row
+    if (vec && T >= 2048 && d <= 1024)
+        layernorm_vec_kernel<DT, 32, 8><<<dim3((T + 7) / 8), 256, 0, stream>>>(pre, n_partials, partial_stride, bias, (const _Float16 *)resid, (O *)y, g, b, T, d, eps);
+    else if (vec)
+        layernorm_vec_kernel<DT, 64, 8><<<grid, 256, 0, stream>>>(pre, n_partials, partial_stride, bias, (const _Float16 *)resid, (O *)y, g, b, T, d, eps);
     else
         layernorm_kernel<DT><<<grid, 256, 0, stream>>>(pre, n_partials, partial_stride, bias, (const _Float16 *)resid, (O *)y, g, b, T, d, eps);
 }
@@ -201,6 +277,21 @@ hipError_t launch_layernorm(const float *pre, int n_partials, int64_t partial_st
         case STI_F32: launch_ln_typed<STI_F32>(pre, n_partials, partial_stride, bias, resid_f16, y, g, b, T, d, eps, vec, stream); break;
         case STI_F16: launch_ln_typed<STI_F16>(pre, n_partials, partial_stride, bias, resid_f16, y, g, b, T, d, eps, vec, stream); break;
         case STI_BF16: launch_ln_typed<STI_BF16>(pre, n_partials, partial_stride, bias, resid_f16, y, g, b, T, d, eps, vec, stream); break;
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_layernorm_f16in(const void *pre_f16, void *y, sti_dtype out_dtype, const float *g,
+                                  const float *b, int T, int d, float eps, hipStream_t stream)
+{
+    if (T <= 0 || d <= 0) return hipSuccess;
+    if (d % 8 || d > 2048) return hipErrorInvalidValue;
+    dim3 grid((T + 3) / 4);
+    const _Float16 *p = (const _Float16 *)pre_f16;
+    switch (out_dtype) {
+        case STI_F32: layernorm_f16in_kernel<STI_F32><<<grid, 256, 0, stream>>>(p, (float *)y, g, b, T, d, eps); break;
+        case STI_F16: layernorm_f16in_kernel<STI_F16><<<grid, 256, 0, stream>>>(p, (_Float16 *)y, g, b, T, d, eps); break;
+        case STI_BF16: layernorm_f16in_kernel<STI_BF16><<<grid, 256, 0, stream>>>(p, (uint16_t *)y, g, b, T, d, eps); break;
     }
     return hipGetLastError();
 }

@@ -89,10 +89,11 @@ hipError_t launch_gemm_f32(const GemmProblem &p, const GemmBlocks &blocks, hipSt
 hipError_t launch_attention_f32(const float *qkv, float *ctx, int B, int L, int m, int dh,
                                 hipStream_t stream);
 
-// binary16 MFMA path (gemm_mfma.hip, attention_mfma.hip): A is binary16; C is binary16
-// (bias, GELU applied) for QKV / FFN_UP and the raw float32 sums for OUT / FFN_DOWN, whose
-// bias and residual are added by launch_layernorm; weights are decoded inside the loader
-// or come from the fragment-tiled working buffer.
+// binary16 MFMA path (gemm_mfma.hip, attention_mfma.hip): A and C are binary16.  QKV / FFN_UP
+// apply bias (and GELU); OUT / FFN_DOWN add bias[N] and the binary16 residual, leaving the
+// LayerNorm to launch_layernorm_f16in.  Weights are decoded inside the loader or come from
+// the fragment-tiled working buffer.  (The few-token variant below leaves float32 partial
+// sums instead, which launch_layernorm completes.)
 hipError_t launch_gemm_mfma(const GemmProblem &p, const GemmBlocks &blocks, hipStream_t stream);
 hipError_t launch_attention_mfma(const void *qkv, void *ctx, int B, int L, int m, int dh,
                                  hipStream_t stream);
@@ -114,6 +115,9 @@ hipError_t launch_layernorm(const float *pre, int n_partials, int64_t partial_st
                             const float *bias, const void *resid_f16, void *y, sti_dtype out_dtype,
                             const float *g, const float *b, int T, int d, float eps,
                             hipStream_t stream);
+// y[t][:] = LayerNorm(pre_f16[t][:]) * g + b for rows that already hold sum + bias + residual.
+hipError_t launch_layernorm_f16in(const void *pre_f16, void *y, sti_dtype out_dtype, const float *g,
+                                  const float *b, int T, int d, float eps, hipStream_t stream);
 // elementwise conversion between activation types
 hipError_t launch_convert(const void *src, sti_dtype src_dtype, void *dst, sti_dtype dst_dtype,
                           uint64_t n, hipStream_t stream);
