@@ -2,11 +2,12 @@
 // every weight is used once and the layer is bound by how fast the packed shards stream in
 // (Section "Submodel execution" runs one input at a time).
 //
-// A workgroup owns one 32-column strip of the output and a range of the K dimension; its
-// four waves take interleaved 64-wide K tiles of that range (split-K inside the workgroup),
+// A workgroup owns one 32-column strip of the output, a 64-row block of tokens and a range of
+// the K dimension; its eight waves take interleaved 64-wide K tiles of that range (split-K
+// inside the workgroup, at most a few tiles per wave, the first two in flight from the start),
 // decode their weights in registers with the shared per-lane loader, read their A fragments
 // straight from global memory (A is a few hundred KiB and cache resident), and reduce the
-// four partial accumulators through LDS.  Long reductions (FFN2) are additionally split
+// eight partial accumulators through LDS.  Long reductions (FFN2) are additionally split
 // across workgroups; those write float32 partial sums that the LayerNorm kernel adds up in
 // a fixed order, so results do not depend on scheduling.
 #include "sti_internal.hpp"
@@ -16,6 +17,8 @@ namespace sti {
 namespace {
 
 constexpr int BK = 64;
+constexpr int NW = 8;            // waves per workgroup
+constexpr int ROWS = 64;         // token rows per workgroup
 
 __device__ inline float gelu_fast(float z)
 {
@@ -33,14 +36,14 @@ __device__ inline float gelu_fast(float z)
 
 template <int RA>
 struct SkinnySmem {
-    float red[4][RA][16][64];                        // partial accumulators of the four waves
+    float red[NW][RA][16][64];                       // partial accumulators of the waves
     uint16_t lut[kMaxShardsPerLayer][kLutEntries];   // codebooks as binary16
-    _Float16 stage[4][32][40];                       // output staging, one 32 x 32 tile per wave
+    _Float16 stage[NW][32][40];                      // output staging, one 32 x 32 tile per wave
 };
 
-// grid: x = 32-column strip, y = K split, z = 128-row block of A
+// grid: x = 32-column strip, y = K split, z = 64-row block of A
 template <int RA>
-__global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmProblem p, GemmBlocks blocks,
+__global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(GemmProblem p, GemmBlocks blocks,
                                                           int k_splits, int64_t partial_stride)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
@@ -52,12 +55,12 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmProblem p, GemmBlo
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int g = lane >> 5, lr = lane & 31;
     const int nw = blockIdx.x * 32;             // first output column of the strip
-    const int m0 = blockIdx.z * 128;            // first token row of this block
+    const int m0 = blockIdx.z * ROWS;           // first token row of this block
     const int split = blockIdx.y;
     const int kt_begin = (int)((int64_t)nkt * split / k_splits);
     const int kt_end = (int)((int64_t)nkt * (split + 1) / k_splits);
 
-    for (int i = tid; i < p.n_blocks * kLutEntries; i += 256) {
+    for (int i = tid; i < p.n_blocks * kLutEntries; i += NW * 64) {
         const int b = i / kLutEntries, e = i % kLutEntries;
         const int bits = blocks.b[b].bits;
         if (bits <= 6 && e < (1 << bits)) sm.lut[b][e] = (uint16_t)f16_bits(blocks.b[b].codebook[e]);
@@ -119,15 +122,18 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmProblem p, GemmBlo
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
 
+    // two tiles in flight before anything else is waited for
     int kt = kt_begin + wave;
-    AStage a_cur;
-    BStage b_cur;
+    AStage a_cur, a_nxt;
+    BStage b_cur, b_nxt;
     if (kt < kt_end) { b_cur = fetch_b(kt); a_cur = fetch_a(kt); }
+    if (kt + NW < kt_end) { b_nxt = fetch_b(kt + NW); a_nxt = fetch_a(kt + NW); }
     __syncthreads();   // codebooks visible
-    for (; kt < kt_end; kt += 4) {
+    for (; kt < kt_end; kt += NW) {
         const BStage bs = b_cur;
         const AStage as = a_cur;
-        if (kt + 4 < kt_end) { b_cur = fetch_b(kt + 4); a_cur = fetch_a(kt + 4); }
+        b_cur = b_nxt; a_cur = a_nxt;
+        if (kt + 2 * NW < kt_end) { b_nxt = fetch_b(kt + 2 * NW); a_nxt = fetch_a(kt + 2 * NW); }
         half8 bf[4];
         decode_raw_any(bs.bits, bs.raw, sm.lut[bs.blk], bf);
 #pragma unroll
@@ -138,7 +144,7 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmProblem p, GemmBlo
                                                                bf[s], acc[i], 0, 0, 0);
     }
 
-    // ---- reduce the four partial accumulators; wave w finishes fragment(s) i == w (mod 4) ----
+    // ---- reduce the partial accumulators; wave i finishes fragment i ----
 #pragma unroll
     for (int i = 0; i < RA; ++i)
 #pragma unroll
@@ -158,12 +164,14 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmProblem p, GemmBlo
     }
 #pragma unroll
     for (int i = 0; i < RA; ++i) {
-        if ((i & 3) != wave) continue;   // wave-uniform
+        if (i != wave) continue;   // wave-uniform
         float sum[16];
 #pragma unroll
         for (int v = 0; v < 16; ++v)
-            sum[v] = (sm.red[0][i][v][lane] + sm.red[1][i][v][lane]) +
-                     (sm.red[2][i][v][lane] + sm.red[3][i][v][lane]);
+            sum[v] = ((sm.red[0][i][v][lane] + sm.red[1][i][v][lane]) +
+                      (sm.red[2][i][v][lane] + sm.red[3][i][v][lane])) +
+                     ((sm.red[4][i][v][lane] + sm.red[5][i][v][lane]) +
+                      (sm.red[6][i][v][lane] + sm.red[7][i][v][lane]));
         if (!n_split) {
             // raw float32 (partial) sums; bias, residual and LayerNorm follow in the row kernel
             float *C = (float *)p.C + (int64_t)split * partial_stride;
@@ -203,7 +211,7 @@ template <int RA>
 hipError_t launch_ra(const GemmProblem &p, const GemmBlocks &blocks, int N, int k_splits,
                      int64_t partial_stride, hipStream_t stream)
 {
-    dim3 grid(N / 32, k_splits, (p.T + 127) / 128);
+    dim3 grid(N / 32, k_splits, (p.T + ROWS - 1) / ROWS);
     static bool attr_set = false;   // more than 64 KiB of dynamic LDS needs an explicit opt-in
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void *)gemm_skinny_kernel<RA>,
@@ -212,7 +220,7 @@ hipError_t launch_ra(const GemmProblem &p, const GemmBlocks &blocks, int N, int 
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    gemm_skinny_kernel<RA><<<grid, dim3(256), sizeof(SkinnySmem<RA>), stream>>>(p, blocks, k_splits,
+    gemm_skinny_kernel<RA><<<grid, dim3(NW * 64), sizeof(SkinnySmem<RA>), stream>>>(p, blocks, k_splits,
                                                                               partial_stride);
     return hipGetLastError();
 }
@@ -224,7 +232,7 @@ int skinny_k_splits(const GemmProblem &p)
     const bool n_split = (p.kind == GEMM_QKV || p.kind == GEMM_FFN_UP);
     if (n_split) return 1;
     const int nkt = p.n_blocks * p.block_cols / BK;
-    int s = nkt / 16;             // keep about four K tiles per wave
+    int s = nkt / (2 * NW);       // about two K tiles per wave
     if (s < 1) s = 1;
     if (s > kSkinnyMaxSplits) s = kSkinnyMaxSplits;
     return s;
@@ -239,8 +247,7 @@ hipError_t launch_gemm_skinny(const GemmProblem &p, const GemmBlocks &blocks, in
     if (N % 32 || p.block_rows % 32 || p.block_cols % BK || p.lda % 8 || p.ldc % 8 || k_splits < 1)
         return hipErrorInvalidValue;
     if (p.T <= 32) return launch_ra<1>(p, blocks, N, k_splits, partial_stride, stream);
-    if (p.T <= 64) return launch_ra<2>(p, blocks, N, k_splits, partial_stride, stream);
-    return launch_ra<4>(p, blocks, N, k_splits, partial_stride, stream);
+    return launch_ra<2>(p, blocks, N, k_splits, partial_stride, stream);
 }
 
 }  // namespace sti
