@@ -163,6 +163,38 @@ def bench_decode(P, torch, S, steps, warmup):
     return res, ds
 
 
+def bench_host_link(P, D, torch, S, steps, warmup):
+    """The same model forward with the shard streams in pinned host memory, through the
+    load || compute pipeline: cold (no preload buffer), with a preload buffer of one layer at
+    full precision, and with one that holds the whole selection (after its first call)."""
+    wl = S.config4()
+    dims = wl.dims
+    prec = P.STI_PREC_F16_MFMA
+    host, params, x = D.upload_workload(wl, host_data=True)
+    store = P.make_store(D.store_from_plan(host))
+    y = torch.empty_like(x)
+    ws = torch.empty(P.sti_workspace_bytes(dims, wl.batch, wl.seq, prec), dtype=torch.uint8, device="cuda")
+    slot = P.sti_pipeline_staging_bytes(dims) // 2
+    staging = torch.empty(4 * slot, dtype=torch.uint8, device="cuda")
+    out = {"workload": "config4 with every shard stream in pinned host memory", "staging_slots": 4}
+    for name, preload_bytes in (("cold", 0), ("preload_one_layer", slot), ("preload_all", 1 << 30)):
+        preload = torch.empty(preload_bytes, dtype=torch.uint8, device="cuda") if preload_bytes else None
+        pipe = P.StiPipeline(dims, preload, staging)
+        for _ in range(max(1, warmup)):
+            stats = pipe.forward(store, params, wl.plan, x, y, prec, ws)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            stats = pipe.forward(store, params, wl.plan, x, y, prec, ws)
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) / steps * 1e3
+        pipe.close()
+        out[name] = {"ms_per_step": round(ms, 4), "tokens_per_s": round(wl.tokens / ms * 1e3, 1),
+                     "preload_bytes": preload_bytes, "bytes_copied_per_step": stats["bytes_copied"],
+                     "link_GBps": round(stats["bytes_copied"] / ms / 1e6, 2)}
+    return out
+
+
 def cpu_baselines(S, wl, ds):
     """The oracle as it stands, on a bounded sample of both workloads."""
     import oracle
@@ -194,6 +226,9 @@ def main():
                     help="print the kernel source hashes that TRAFFIC is keyed on and exit")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (reference for HBM byte counters)")
+    ap.add_argument("--host-link", action="store_true",
+                    help="also time the load || compute pipeline with the shard streams in pinned host "
+                         "memory (reported beside the headline value, never as it)")
     args = ap.parse_args()
     if args.print_source_hashes:
         for k, t in TRAFFIC.items():
@@ -232,6 +267,8 @@ def main():
         "kernel_ms_per_step": model["kernel_ms_per_step"],
         "decode": decode,
     }
+    if args.host_link:
+        line["host_link_pipeline"] = bench_host_link(P, D, torch, S, args.steps, args.warmup)
     if not args.no_cpu_baseline:
         cpu_model, cpu_dec = cpu_baselines(S, wl, ds)
         line["cpu_baseline"] = cpu_model

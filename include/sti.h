@@ -189,6 +189,62 @@ sti_status sti_model_forward(const sti_dims *dims, int n_layers, const sti_shard
                              void *hip_stream);
 
 /* ---------------------------------------------------------------------------
+ * Layerwise load || compute pipeline with a preload buffer (Section "Elastic
+ * pipelining": the IO of layer k+1 overlaps the computation of layer k, and a small
+ * preload buffer keeps the shards of the bottom layers in memory across inferences;
+ * Section "Submodel execution": after an inference the loaded shards are kept from
+ * the bottom layers up until the buffer is full).
+ *
+ * Here the packed shard streams stay in HOST memory (pinned, so that copies are
+ * asynchronous) and play the role of the paper's flash.  sti_pipeline_forward
+ * computes exactly what sti_model_forward computes, but moves the selected version
+ * of every shard of layer k+1 over the host link on a library-owned stream while
+ * the caller's stream computes layer k.  The first selected shards in (layer,
+ * shard) order that fit `preload_bytes` are placed in the preload buffer instead of
+ * the two staging slots; a later call that selects the same versions from the same
+ * host addresses finds them there and copies nothing for them.
+ *
+ *  preload_buffer DEVICE, 256-byte aligned, owned by the caller, must outlive the handle;
+ *                 may be NULL with preload_bytes == 0 (every call starts cold).
+ *  staging        DEVICE, 256-byte aligned, owned by the caller, must outlive the handle.
+ *                 sti_pipeline_staging_bytes(dims) is the minimum: two slots of one
+ *                 full-precision layer each.  Every further slot that fits (up to 8)
+ *                 lets the copies run one more layer ahead of the computation.
+ *  store          as for sti_model_forward, except that `data` of every version is a
+ *                 HOST address (16-byte aligned); codebooks and outlier dictionaries
+ *                 stay DEVICE resident like the biases (a few hundred bytes each).
+ *  stats          HOST, optional: what this call copied and what it found resident.
+ *
+ * A handle serves one call at a time; calls on one handle may be enqueued back to
+ * back (the copies of a call wait for the kernels of the previous one).  The
+ * library-owned stream has default priority; the handle must not be used while a
+ * stream capture is active.  Errors as for sti_model_forward.
+ * ------------------------------------------------------------------------- */
+typedef struct sti_pipeline sti_pipeline;
+
+typedef struct {
+    uint64_t bytes_copied;     /* host -> device bytes moved by this call                    */
+    uint64_t bytes_resident;   /* bytes of the selected shards held by the preload buffer     */
+    uint32_t shards_copied;    /* shards moved over the host link by this call                */
+    uint32_t shards_hit;       /* selected shards found in the preload buffer (no copy)       */
+    uint32_t shards_preloaded; /* selected shards in the preload buffer after this call       */
+} sti_pipeline_stats;
+
+size_t sti_pipeline_staging_bytes(const sti_dims *dims);
+
+sti_status sti_pipeline_create(const sti_dims *dims, void *preload_buffer, size_t preload_bytes,
+                               void *staging, size_t staging_bytes, sti_pipeline **out);
+
+sti_status sti_pipeline_forward(sti_pipeline *pipeline, int n_layers, const sti_shard *store,
+                                const sti_layer_params *params, const int8_t *plan, const void *x,
+                                void *y, sti_dtype io_dtype, int batch, int seq,
+                                sti_precision precision, void *workspace, size_t workspace_bytes,
+                                void *hip_stream, sti_pipeline_stats *stats);
+
+/* Waits for the handle's copies, then releases its stream and events (not the buffers). */
+sti_status sti_pipeline_destroy(sti_pipeline *pipeline);
+
+/* ---------------------------------------------------------------------------
  * Per-kernel timing (the counterpart of the paper's one-time hardware profiling
  * of computation delays, Section "Prerequisite: offline profiling").  Between
  * sti_profile_begin() and sti_profile_end() every kernel launch of the entry

@@ -42,6 +42,12 @@ class StiProfile(C.Structure):
     _fields_ = [("launches", C.c_uint64 * 8), ("ms", C.c_double * 8)]
 
 
+class StiPipelineStats(C.Structure):
+    _fields_ = [("bytes_copied", C.c_uint64), ("bytes_resident", C.c_uint64),
+                ("shards_copied", C.c_uint32), ("shards_hit", C.c_uint32),
+                ("shards_preloaded", C.c_uint32)]
+
+
 class StiError(RuntimeError):
     def __init__(self, status: int, where: str):
         self.status = status
@@ -73,6 +79,18 @@ def _load():
             C.POINTER(StiDims), C.c_int, C.POINTER(StiShard), C.POINTER(StiLayerParams),
             C.POINTER(C.c_int8), C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int,
             C.c_void_p, C.c_size_t, C.c_void_p]
+    L.sti_pipeline_staging_bytes.restype = C.c_size_t
+    L.sti_pipeline_staging_bytes.argtypes = [C.POINTER(StiDims)]
+    L.sti_pipeline_create.restype = C.c_int
+    L.sti_pipeline_create.argtypes = [C.POINTER(StiDims), C.c_void_p, C.c_size_t, C.c_void_p,
+                                      C.c_size_t, C.POINTER(C.c_void_p)]
+    L.sti_pipeline_forward.restype = C.c_int
+    L.sti_pipeline_forward.argtypes = [
+        C.c_void_p, C.c_int, C.POINTER(StiShard), C.POINTER(StiLayerParams), C.POINTER(C.c_int8),
+        C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_size_t,
+        C.c_void_p, C.POINTER(StiPipelineStats)]
+    L.sti_pipeline_destroy.restype = C.c_int
+    L.sti_pipeline_destroy.argtypes = [C.c_void_p]
     L.sti_profile_begin.restype = C.c_int
     L.sti_profile_begin.argtypes = []
     L.sti_profile_end.restype = C.c_int
@@ -228,3 +246,57 @@ def sti_profile_end() -> dict:
     if st != 0:
         raise StiError(st, "sti_profile_end")
     return {name: (int(prof.launches[i]), float(prof.ms[i])) for i, name in enumerate(KERNEL_CLASSES)}
+
+
+def sti_pipeline_staging_bytes(dims) -> int:
+    d = make_dims(dims)
+    return int(lib.sti_pipeline_staging_bytes(C.byref(d)))
+
+
+class StiPipeline:
+    """Handle of the load || compute pipeline.  ``preload`` and ``staging`` are CUDA uint8
+    tensors that must stay alive as long as the handle."""
+
+    def __init__(self, dims, preload, staging):
+        self._dims = make_dims(dims)
+        self._keep = (preload, staging)
+        handle = C.c_void_p()
+        pre_bytes = 0 if preload is None else preload.numel() * preload.element_size()
+        st = lib.sti_pipeline_create(C.byref(self._dims), _ptr(preload), pre_bytes, _ptr(staging),
+                                     staging.numel() * staging.element_size(), C.byref(handle))
+        if st != 0:
+            raise StiError(st, "sti_pipeline_create")
+        self._h = handle
+
+    def forward(self, store, params: Sequence, plan, x, y, precision: int, workspace, stream=None) -> dict:
+        """store: make_store(...) of versions whose ``data`` are pinned host tensors."""
+        import numpy as np
+        plan = np.ascontiguousarray(plan, dtype=np.int8)
+        n_layers = int(plan.shape[0]) if plan.ndim == 2 else 0
+        if not isinstance(store, C.Array):
+            store = make_store(store)
+        ps = (StiLayerParams * max(1, n_layers))()
+        for l in range(n_layers):
+            ps[l] = make_params(params[l])
+        stats = StiPipelineStats()
+        ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+        st = lib.sti_pipeline_forward(self._h, n_layers, store, ps,
+                                      plan.ctypes.data_as(C.POINTER(C.c_int8)), _ptr(x), _ptr(y),
+                                      _dtype_code(x), int(x.shape[0]), int(x.shape[1]), int(precision),
+                                      _ptr(workspace), ws_bytes, _stream_handle(stream), C.byref(stats))
+        if st != 0:
+            raise StiError(st, "sti_pipeline_forward")
+        return {n: int(getattr(stats, n)) for n, _ in StiPipelineStats._fields_}
+
+    def close(self):
+        if self._h:
+            st = lib.sti_pipeline_destroy(self._h)
+            self._h = None
+            if st != 0:
+                raise StiError(st, "sti_pipeline_destroy")
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

@@ -6,13 +6,10 @@
 #include <vector>
 
 #include "sti_internal.hpp"
+#include "api_internal.hpp"
 
 namespace sti {
-namespace {
 
-inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
-
-inline bool valid_packed_bits(int b) { return b >= 2 && b <= 6; }
 
 // Pinned host ring through which shard tables larger than the inline limit are
 // uploaded.  A slot is reused only after the copy that read it has completed.
@@ -174,11 +171,6 @@ sti_status check_decode_shard(const sti_shard &s)
 // Layer sequencing
 // ---------------------------------------------------------------------------
 
-inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
-
-struct WorkspaceLayout {
-    size_t w32 = 0, w16 = 0, act[2] = {0, 0}, qkv = 0, ctx = 0, pre = 0, h = 0, u = 0, total = 0;
-};
 
 // Offsets of the scratch regions of one layer call (sized for all M shards present).
 WorkspaceLayout workspace_layout(const sti_dims &d, int64_t T, sti_precision prec)
@@ -260,10 +252,6 @@ inline const void *block_start(const sti_shard &s, size_t elem_off)
 // used by at most a few row tiles).
 constexpr int kWorkingBufferMinTokens = 512;
 
-#define STI_TRY(expr)                          \
-    do {                                       \
-        if ((expr) != hipSuccess) return STI_ERR_HIP; \
-    } while (0)
 
 // One layer, arguments already validated.  `in` is float32 (F32 precision) or
 // binary16 (MFMA precision); `out` is written as out_dtype.
@@ -408,7 +396,6 @@ sti_status check_io(const void *x, void *y, sti_dtype io, int64_t T, int d)
     return STI_OK;
 }
 
-}  // namespace
 }  // namespace sti
 
 using namespace sti;

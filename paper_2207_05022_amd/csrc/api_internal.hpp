@@ -1,0 +1,33 @@
+// Host-side helpers shared by the entry points in api.hip and pipeline.hip.
+#pragma once
+#include "sti_internal.hpp"
+
+namespace sti {
+
+inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+inline bool valid_packed_bits(int b) { return b >= 2 && b <= 6; }
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+#define STI_TRY(expr)                                 \
+    do {                                              \
+        if ((expr) != hipSuccess) return STI_ERR_HIP; \
+    } while (0)
+
+// Offsets of the scratch regions of one layer call inside the caller's workspace.
+struct WorkspaceLayout {
+    size_t w32 = 0, w16 = 0, act[2] = {0, 0}, qkv = 0, ctx = 0, pre = 0, h = 0, u = 0, total = 0;
+};
+WorkspaceLayout workspace_layout(const sti_dims &d, int64_t T, sti_precision prec);
+
+sti_status check_dims(const sti_dims *dims, int batch, int seq, sti_precision prec);
+sti_status check_decode_shard(const sti_shard &s);   // bitwidth 2..6 or 32, pointers, alignment
+sti_status check_params(const sti_layer_params *p);
+sti_status check_io(const void *x, void *y, sti_dtype io, int64_t T, int d);
+
+// One layer over shards[M] (bitwidth 0 = absent), arguments already validated.  `in` is
+// float32 (F32 precision) or binary16 (MFMA precision); `out` is written as out_dtype.
+sti_status run_layer(const sti_dims &d, const sti_shard *shards, const sti_layer_params &prm,
+                     const void *in, void *out, sti_dtype out_dtype, int B, int Lseq,
+                     sti_precision prec, uint8_t *ws, const WorkspaceLayout &wl, hipStream_t stream);
+
+}  // namespace sti

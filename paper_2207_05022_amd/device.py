@@ -12,15 +12,23 @@ import numpy as np
 import torch
 
 
-def upload_shard(sh, device="cuda"):
-    """sh: object with bitwidth, data (numpy uint8 / float32), codebook (numpy float32 or None)."""
+def upload_shard(sh, device="cuda", host_data=False):
+    """sh: object with bitwidth, data (numpy uint8 / float32), codebook (numpy float32 or None).
+    With ``host_data`` the stream stays in host memory for the load || compute pipeline (pinned,
+    or ordinary memory when ``host_data == "pageable"``); dictionaries always go to the device."""
     if sh is None:
         return None
+    if host_data == "pageable":
+        place = lambda t: t.clone()
+    elif host_data:
+        place = lambda t: t.pin_memory()
+    else:
+        place = lambda t: t.to(device)
     if sh.bitwidth == 32:
-        data = torch.from_numpy(np.ascontiguousarray(sh.data, dtype=np.float32)).to(device)
+        data = place(torch.from_numpy(np.ascontiguousarray(sh.data, dtype=np.float32)))
         cb = None
     else:
-        data = torch.from_numpy(np.ascontiguousarray(sh.data, dtype=np.uint8)).to(device)
+        data = place(torch.from_numpy(np.ascontiguousarray(sh.data, dtype=np.uint8)))
         cb = torch.from_numpy(np.ascontiguousarray(sh.codebook, dtype=np.float32)).to(device)
     pos = val = None
     if getattr(sh, "outlier_pos", None) is not None and len(sh.outlier_pos):
@@ -36,9 +44,9 @@ def upload_params(p, device="cuda"):
                               for n in names})
 
 
-def upload_workload(wl, device="cuda"):
+def upload_workload(wl, device="cuda", host_data=False):
     """Returns (shards [n_layers][M] with None = absent, params [n_layers], x tensor)."""
-    shards = [[upload_shard(s, device) for s in row] for row in wl.shards]
+    shards = [[upload_shard(s, device, host_data) for s in row] for row in wl.shards]
     params = [upload_params(p, device) for p in wl.params]
     x = torch.from_numpy(np.ascontiguousarray(wl.x)).to(device)
     return shards, params, x

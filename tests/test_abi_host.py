@@ -146,3 +146,27 @@ def test_model_argument_errors(P):
     wrong = (P.StiShard * 12)(*[shard(P, 5) for _ in range(12)])
     assert call([4, 0], store=wrong) == 3           # slot holds another bitwidth
     assert call([4, 0], n_layers=-1) == 2
+
+
+def test_pipeline_argument_errors(P):
+    """Everything sti_pipeline_create rejects is rejected before a stream is created."""
+    d = P.binding.make_dims(Dims(d=768, M=12, dh=64, f=256))
+    need = P.lib.sti_pipeline_staging_bytes(C.byref(d))
+    assert need == 2 * 12 * 768 * (4 * 64 + 2 * 256) * 4      # two slots of one full-precision layer
+    assert P.lib.sti_pipeline_staging_bytes(None) == 0
+    bad = P.binding.make_dims(Dims(d=768, M=0, dh=64, f=256))
+    assert P.lib.sti_pipeline_staging_bytes(C.byref(bad)) == 0
+    h = C.c_void_p()
+    create = P.lib.sti_pipeline_create
+    assert create(None, None, 0, FAKE, need, C.byref(h)) == 1
+    assert create(C.byref(d), None, 0, FAKE, need, None) == 1
+    assert create(C.byref(bad), None, 0, FAKE, need, C.byref(h)) == 2
+    assert create(C.byref(d), None, 0, FAKE, need - 1, C.byref(h)) == 6
+    assert create(C.byref(d), None, 0, None, need, C.byref(h)) == 6
+    assert create(C.byref(d), None, 4096, FAKE, need, C.byref(h)) == 1     # bytes without a buffer
+    assert create(C.byref(d), FAKE + 8, 4096, FAKE, need, C.byref(h)) == 5
+    assert create(C.byref(d), None, 0, FAKE + 16, need, C.byref(h)) == 5
+    assert not h.value
+    assert P.lib.sti_pipeline_forward(None, 0, None, None, None, None, None, 0, 0, 0, 0, None, 0, None,
+                                      None) == 1
+    assert P.lib.sti_pipeline_destroy(None) == 0
