@@ -51,18 +51,16 @@ struct Smem {
     uint16_t lut[kMaxShardsPerLayer][kLutEntries];
 };
 
-template <int RA, int RB, int WM, int WN, bool TILED>
+template <int KIND, int RA, int RB, int WM, int WN, bool TILED>
 __global__ __launch_bounds__(256, (RA * RB >= 4 ? 2 : 3)) void gemm_mfma_kernel(GemmProblem p, GemmBlocks blocks)
 {
     static_assert(WM * WN == 4, "four waves per workgroup");
     constexpr int BM = WM * RA * 32, BN = WN * RB * 32;
     constexpr int A_PASSES = BM / 32;   // 16-byte pieces per thread per K tile
-    constexpr int LDC = RB * 32 + 8;    // padded row of the output staging tile (halves)
-    static_assert(4 * 32 * LDC <= 2 * BM * LDA, "output staging fits in the A buffers");
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     Smem<BM> &sm = *reinterpret_cast<Smem<BM> *>(smem_raw);
 
-    const bool n_split = (p.kind == GEMM_QKV || p.kind == GEMM_FFN_UP);
+    constexpr bool n_split = (KIND == GEMM_QKV || KIND == GEMM_FFN_UP);
     const int N = n_split ? p.n_blocks * p.block_rows : p.block_rows;
     const int K = n_split ? p.block_cols : p.n_blocks * p.block_cols;
     const int nkt = K / BK;
@@ -173,17 +171,32 @@ __global__ __launch_bounds__(256, (RA * RB >= 4 ? 2 : 3)) void gemm_mfma_kernel(
             if constexpr (TILED) decode_raw<16>(st.raw[r], lut, bf[r]);
             else decode_raw_any(st.bits, st.raw[r], lut, bf[r]);
         }
+        // the A fragments of k-step s+1 are read from LDS while the MFMAs of step s run;
+        // the scheduling barriers keep the reads ahead of the MFMAs they overlap
+        half8 a_cur[RA], a_nxt[RA];
+#pragma unroll
+        for (int i = 0; i < RA; ++i) a_cur[i] = *(const half8 *)&sm.a[buf][mw + i * 32 + lr][g * 32];
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
+            if (s < 3) {
 #pragma unroll
-            for (int i = 0; i < RA; ++i) {
-                half8 a = *(const half8 *)&sm.a[buf][mw + i * 32 + lr][g * 32 + s * 8];
+                for (int i = 0; i < RA; ++i)
+                    a_nxt[i] = *(const half8 *)&sm.a[buf][mw + i * 32 + lr][g * 32 + (s + 1) * 8];
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int i = 0; i < RA; ++i)
 #pragma unroll
                 for (int r = 0; r < RB; ++r)
-                    acc[i][r] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, bf[r][s], acc[i][r], 0, 0, 0);
+                    acc[i][r] = __builtin_amdgcn_mfma_f32_32x32x16_f16(bf[r][s], a_cur[i], acc[i][r], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            if (s < 3) {
+#pragma unroll
+                for (int i = 0; i < RA; ++i) a_cur[i] = a_nxt[i];
             }
         }
     };
+
 
     AStage a0;
     BStage b0;
@@ -198,103 +211,99 @@ __global__ __launch_bounds__(256, (RA * RB >= 4 ? 2 : 3)) void gemm_mfma_kernel(
         compute(kt & 1, cur);
     }
 
-    // ---- epilogue: lane owns column lr of each strip, rows (v/4)*8 + g*4 + v%4 of each fragment ----
-    if (p.kind == GEMM_OUT || p.kind == GEMM_FFN_DOWN) {
-        // sums + bias + residual, rounded once to binary16; LayerNorm follows in the row kernel.
-        // Staged through LDS in float32 so that residual loads and stores are 16-byte row pieces.
-        constexpr int LDF = RB * 32 + 4;   // padded float32 staging row
-        static_assert(4 * 32 * LDF * 2 <= 2 * BM * LDA, "float32 staging fits in the A buffers");
-        __syncthreads();   // every wave is done with the A tiles
-        float *stage = (float *)&sm.a[0][0][0] + wave * (32 * LDF);
-        _Float16 *C = (_Float16 *)p.C;
-        const _Float16 *R = (const _Float16 *)p.resid;
-#pragma unroll
-        for (int i = 0; i < RA; ++i) {
-#pragma unroll
-            for (int r = 0; r < RB; ++r)
-#pragma unroll
-                for (int v = 0; v < 16; ++v)
-                    stage[((v >> 2) * 8 + g * 4 + (v & 3)) * LDF + r * 32 + lr] = acc[i][r][v];
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-#pragma unroll
-            for (int j = 0; j < 2 * RB; ++j) {
-                const int c = lane + 64 * j;              // 8-column piece of the 32 x (RB*32) tile
-                const int row = c / (RB * 4), cc = c % (RB * 4);
-                const int m = m0 + mw + i * 32 + row;
-                const int n = nw + cc * 8;
-                if (wave_active && m < p.T) {
-                    const f32x4 s0 = *(const f32x4 *)(stage + row * LDF + cc * 8);
-                    const f32x4 s1 = *(const f32x4 *)(stage + row * LDF + cc * 8 + 4);
-                    const f32x4 b0 = *(const f32x4 *)(p.bias0 + n), b1 = *(const f32x4 *)(p.bias0 + n + 4);
-                    const half8 rr = *(const half8 *)(R + (int64_t)m * p.ldr + n);
-                    half8 o;
-                    o[0] = (_Float16)(s0.x + b0.x + (float)rr[0]); o[1] = (_Float16)(s0.y + b0.y + (float)rr[1]);
-                    o[2] = (_Float16)(s0.z + b0.z + (float)rr[2]); o[3] = (_Float16)(s0.w + b0.w + (float)rr[3]);
-                    o[4] = (_Float16)(s1.x + b1.x + (float)rr[4]); o[5] = (_Float16)(s1.y + b1.y + (float)rr[5]);
-                    o[6] = (_Float16)(s1.z + b1.z + (float)rr[6]); o[7] = (_Float16)(s1.w + b1.w + (float)rr[7]);
-                    *(half8 *)(C + (int64_t)m * p.ldc + n) = o;
-                }
-            }
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        }
-        return;
-    }
-
-    float bias[RB];
+    // ---- epilogue ----
+    // The weight fragment is the first MFMA operand, so the accumulator of a 32 x 32 block holds,
+    // in lane l, token row lr and output columns (v/4)*8 + g*4 + v%4.  Exchanging registers
+    // between lanes l and l+32 (v_permlane32_swap) turns that into runs of 8 consecutive columns
+    // per lane: after the swap of the column groups 2q and 2q+1 the lane owns columns
+    // 16q + 8g .. +8 of its row, i.e. one 16-byte piece of the output row.  Bias, GELU and the
+    // residual are applied to that piece in registers; the pieces of the whole workgroup tile
+    // are then collected in LDS so that every global store instruction writes whole rows of
+    // the tile (stores of 32-byte row segments straight from the accumulator layout were
+    // measured to be limited by the number of partial cache lines per instruction).
+    constexpr int LDT = BN + 8;   // padded row of the staged tile (halves): conflict-free 16-byte writes
+    static_assert(BM * LDT <= 2 * BM * LDA, "the staged tile fits in the A buffers");
+    _Float16 *tile_out = &sm.a[0][0][0];
+    const _Float16 *R = (const _Float16 *)p.resid;
+    __syncthreads();   // every wave is done with the A tiles
 #pragma unroll
     for (int r = 0; r < RB; ++r) {
-        const int nrow = nrow0 + r * 32 + lr;
-        if (p.kind == GEMM_QKV) {
-            const int which = nrow / p.d_head, e = nrow - which * p.d_head;
-            const float *bp = which == 0 ? p.bias0 : (which == 1 ? p.bias1 : p.bias2);
-            bias[r] = bp[blocks.b[nblk].shard * p.d_head + e];
-        } else {
-            bias[r] = p.bias0[blocks.b[nblk].shard * p.block_rows + nrow];
+        f32x4 bias[2][2];
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            const int c = r * 32 + 16 * q + 8 * g;     // first column of the piece inside the wave's strip
+            const float *bp;
+            if constexpr (KIND == GEMM_QKV) {
+                const int nrow = nrow0 + c;
+                const int which = nrow / p.d_head, e0 = nrow - which * p.d_head;
+                bp = (which == 0 ? p.bias0 : (which == 1 ? p.bias1 : p.bias2)) + blocks.b[nblk].shard * p.d_head + e0;
+            } else if constexpr (KIND == GEMM_FFN_UP) {
+                bp = p.bias0 + blocks.b[nblk].shard * p.block_rows + nrow0 + c;
+            } else {
+                bp = p.bias0 + nw + c;
+            }
+            bias[q][0] = *(const f32x4 *)bp;
+            bias[q][1] = *(const f32x4 *)(bp + 4);
+        }
+#pragma unroll
+        for (int i = 0; i < RA; ++i) {
+            const int row = mw + i * 32 + lr;          // row inside the tile
+            half8 res[2];
+            if constexpr (!n_split) {
+                const int m = m0 + row;
+#pragma unroll
+                for (int q = 0; q < 2; ++q) {
+                    u32x4 v = {0, 0, 0, 0};
+                    if (wave_active && m < p.T) v = *(const u32x4 *)(R + (int64_t)m * p.ldr + nw + r * 32 + 16 * q + 8 * g);
+                    res[q] = __builtin_bit_cast(half8, v);
+                }
+            }
+#pragma unroll
+            for (int q = 0; q < 2; ++q) {
+                float x[8];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    // (element values first: a bit cast applied to a vector element itself reads element 0)
+                    const float lo = acc[i][r][(2 * q) * 4 + e], hi = acc[i][r][(2 * q + 1) * 4 + e];
+                    const auto sw = __builtin_amdgcn_permlane32_swap(__builtin_bit_cast(uint32_t, lo),
+                                                                     __builtin_bit_cast(uint32_t, hi), false, false);
+                    const uint32_t s0 = sw[0], s1 = sw[1];
+                    x[e] = __builtin_bit_cast(float, s0);
+                    x[4 + e] = __builtin_bit_cast(float, s1);
+                }
+                half8 o;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    float y = x[e] + bias[q][e >> 2][e & 3];
+                    if constexpr (KIND == GEMM_FFN_UP) y = gelu_fast(y);
+                    if constexpr (!n_split) y += (float)res[q][e];
+                    o[e] = (_Float16)y;
+                }
+                *(half8 *)(tile_out + row * LDT + (wn * RB + r) * 32 + 16 * q + 8 * g) = o;
+            }
         }
     }
-    __syncthreads();   // every wave is done with the A tiles; reuse them as output staging
-    // each wave stages through a region of its own; LDS serves one wave's requests in order,
-    // so no barrier is needed between its writes and its reads
-    _Float16 *stage = &sm.a[0][0][0] + wave * (32 * LDC);
+    __syncthreads();
+    // 16 lanes per tile row: one store instruction writes 4 whole rows of the tile
     _Float16 *C = (_Float16 *)p.C;
+    constexpr int PIECES_PER_ROW = BN / 8;
+    constexpr int PASSES = BM * PIECES_PER_ROW / 256;
+    u32x4 piece[PASSES];
 #pragma unroll
-    for (int i = 0; i < RA; ++i) {
+    for (int j = 0; j < PASSES; ++j) {
+        const int pc = tid + 256 * j;
+        piece[j] = *(const u32x4 *)(tile_out + (pc / PIECES_PER_ROW) * LDT + (pc % PIECES_PER_ROW) * 8);
+    }
 #pragma unroll
-        for (int r = 0; r < RB; ++r)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                float x = acc[i][r][v] + bias[r];
-                if (p.kind == GEMM_FFN_UP) x = gelu_fast(x);
-                stage[((v >> 2) * 8 + g * 4 + (v & 3)) * LDC + r * 32 + lr] = (_Float16)x;
-            }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        u32x4 chunk[2 * RB];
-#pragma unroll
-        for (int j = 0; j < 2 * RB; ++j) {
-            const int c = lane + 64 * j;              // 16-byte chunk of the 32 x (RB*32) tile
-            chunk[j] = *(const u32x4 *)(stage + (c / (RB * 4)) * LDC + (c % (RB * 4)) * 8);
-        }
-#pragma unroll
-        for (int j = 0; j < 2 * RB; ++j) {
-            const int c = lane + 64 * j;
-            const int row = c / (RB * 4), cc = c % (RB * 4);
-            const int m = m0 + mw + i * 32 + row;
-            if (wave_active && m < p.T) *(u32x4 *)(C + (int64_t)m * p.ldc + nw + cc * 8) = chunk[j];
-        }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    for (int j = 0; j < PASSES; ++j) {
+        const int pc = tid + 256 * j;
+        const int m = m0 + pc / PIECES_PER_ROW, n = tile_n * BN + (pc % PIECES_PER_ROW) * 8;
+        if (m < p.T && n < N) *(u32x4 *)(C + (int64_t)m * p.ldc + n) = piece[j];
     }
 }
 
-template <int RA, int RB, int WM, int WN>
-hipError_t launch_cfg(const GemmProblem &p, const GemmBlocks &blocks, int N, hipStream_t stream)
+template <int KIND, int RA, int RB, int WM, int WN>
+hipError_t launch_kind(const GemmProblem &p, const GemmBlocks &blocks, int N, hipStream_t stream)
 {
     constexpr int BM = WM * RA * 32, BN = WN * RB * 32;
     const int total = ((N + BN - 1) / BN) * ((p.T + BM - 1) / BM);
@@ -302,10 +311,22 @@ hipError_t launch_cfg(const GemmProblem &p, const GemmBlocks &blocks, int N, hip
     bool tiled = p.n_blocks > 0;
     for (int b = 0; b < p.n_blocks; ++b) tiled = tiled && blocks.b[b].bits == kTiledBits;
     if (tiled)
-        gemm_mfma_kernel<RA, RB, WM, WN, true><<<grid, dim3(256), sizeof(Smem<BM>), stream>>>(p, blocks);
+        gemm_mfma_kernel<KIND, RA, RB, WM, WN, true><<<grid, dim3(256), sizeof(Smem<BM>), stream>>>(p, blocks);
     else
-        gemm_mfma_kernel<RA, RB, WM, WN, false><<<grid, dim3(256), sizeof(Smem<BM>), stream>>>(p, blocks);
+        gemm_mfma_kernel<KIND, RA, RB, WM, WN, false><<<grid, dim3(256), sizeof(Smem<BM>), stream>>>(p, blocks);
     return hipGetLastError();
+}
+
+template <int RA, int RB, int WM, int WN>
+hipError_t launch_cfg(const GemmProblem &p, const GemmBlocks &blocks, int N, hipStream_t stream)
+{
+    switch (p.kind) {
+    case GEMM_QKV: return launch_kind<GEMM_QKV, RA, RB, WM, WN>(p, blocks, N, stream);
+    case GEMM_FFN_UP: return launch_kind<GEMM_FFN_UP, RA, RB, WM, WN>(p, blocks, N, stream);
+    case GEMM_OUT: return launch_kind<GEMM_OUT, RA, RB, WM, WN>(p, blocks, N, stream);
+    case GEMM_FFN_DOWN: return launch_kind<GEMM_FFN_DOWN, RA, RB, WM, WN>(p, blocks, N, stream);
+    }
+    return hipErrorInvalidValue;
 }
 
 }  // namespace
@@ -317,6 +338,7 @@ hipError_t launch_gemm_mfma(const GemmProblem &p, const GemmBlocks &blocks, hipS
     if (p.T <= 0 || N <= 0) return hipSuccess;
     if (N % 64 || p.block_rows % 64 || p.block_cols % BK || p.lda % 8 || p.ldc % 8)
         return hipErrorInvalidValue;
+    if (gemm_wide_supported(p, blocks)) return launch_gemm_wide(p, blocks, stream);
     // Wide outputs (QKV, FFN1) take 128-row tiles; the d-wide outputs (O, FFN2) take 64-row
     // tiles so that the grid still covers the chip.
     if (N >= 2048 && p.T > 64) return launch_cfg<4, 1, 1, 4>(p, blocks, N, stream);

@@ -1,0 +1,387 @@
+// Projections of the layer on the matrix cores for many tokens (Section "A primer on
+// transformer": the Q/K/V, output and two FFN linear layers), with the weights taken from
+// the per-layer fragment-tiled binary16 working buffer (Section "Submodel execution": a
+// layer's shards are decompressed into a working buffer before the layer runs).
+//
+//   C[T x N] = A[T x K] * W^T,  float32 accumulation in v_mfma_f32_32x32x16_f16.
+//
+// One workgroup of NW waves owns a (RA*32) x (NW*32) tile and is sized so that a compute
+// unit holds all its waves at once (12 wave slots at this register budget): all waves of a
+// unit then move through the K loop in step, share one copy of the A tile and finish together.
+//   - the A tile [BM x 64] goes global -> LDS directly (global_load_lds_dwordx4, no
+//     registers, no LDS store instructions), two stages; its 16-byte chunks are XOR-swizzled
+//     by row pair so that the unpadded rows read without bank conflicts;
+//   - a wave's weight fragments are contiguous 1 KiB loads from the working buffer, one K
+//     tile ahead, straight into registers;
+//   - the A fragments of k-step s+1 are read from LDS while the MFMAs of step s run;
+//   - the weight fragment is the first MFMA operand, so a lane's accumulators are runs of
+//     output columns of one token row; v_permlane32_swap merges them into 16-byte pieces,
+//     which get bias / GELU / residual in registers and leave through an LDS copy of the
+//     whole tile, so that every global store instruction writes whole rows of the tile.
+#include "sti_internal.hpp"
+#include "weight_loader.hpp"
+
+namespace sti {
+namespace {
+
+constexpr int BK = 64;   // K positions per LDS stage
+
+typedef __attribute__((address_space(1))) const void global_cptr;
+typedef __attribute__((address_space(3))) void lds_ptr;
+
+// GELU with the Gaussian CDF (the erf form, not the tanh form):  z * Phi(z),
+// Phi(z) = 1/2 + z * R(z^2).  R is a degree-8 polynomial in u = 2 z^2 / 4.5^2 - 1, fitted in
+// float64 (weighted least squares on Chebyshev nodes) to (Phi(z) - 1/2) / z on |z| <= 4.5;
+// beyond that Phi is taken at the clamped argument (1 - Phi(4.5) = 3.4e-6).  Evaluated in
+// float32 the absolute error of the result is below 5e-5 for all z (0.1 of a binary16 ulp at
+// 0.35, the value at z = 0.6 where the error peaks) and its relative error below 1e-4 for
+// z > -1; 13 arithmetic instructions per value and no transcendental ones, which matters
+// because the epilogue of the FFN1 projection is bound by exactly these instructions.
+__device__ inline float gelu_erf(float z)
+{
+    const float zc = __builtin_amdgcn_fmed3f(z, -4.5f, 4.5f);
+    const float u = fmaf(zc * zc, 2.0f / 20.25f, -1.0f);
+    float r = 3.174704981e-03f;
+    r = fmaf(r, u, -9.158361878e-03f);
+    r = fmaf(r, u, 1.244540513e-02f);
+    r = fmaf(r, u, -1.696567595e-02f);
+    r = fmaf(r, u, 2.754268719e-02f);
+    r = fmaf(r, u, -4.047719455e-02f);
+    r = fmaf(r, u, 5.482644199e-02f);
+    r = fmaf(r, u, -7.717846451e-02f);
+    r = fmaf(r, u, 1.569020774e-01f);
+    return z * fmaf(zc, r, 0.5f);
+}
+
+template <int RA, int NW>
+constexpr size_t wide_lds_bytes()
+{
+    constexpr size_t stages = 3 * (size_t)(RA * 32) * BK * 2;
+    constexpr size_t tile = (size_t)(RA * 32) * (NW * 32 + 8) * 2;
+    return stages > tile ? stages : tile;
+}
+
+template <int KIND, int RA, int NW>
+__global__ __launch_bounds__(NW * 64, 3) void gemm_wide_kernel(GemmProblem p, GemmBlocks blocks)
+{
+    constexpr int BM = RA * 32, BN = NW * 32, NT = NW * 64;
+    constexpr bool n_split = (KIND == GEMM_QKV || KIND == GEMM_FFN_UP);
+    constexpr int STAGE = BM * BK;              // halves per A stage
+    constexpr int FETCHES = BM / 8;             // fetch instructions per A stage: 8 rows (1 KiB) each
+    constexpr int FPW = (FETCHES + NW - 1) / NW;   // per wave: wave w issues fetches w, w + NW, ...
+    extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
+    _Float16 *a_lds = (_Float16 *)smem_raw;
+
+    const int N = n_split ? p.n_blocks * p.block_rows : p.block_rows;
+    const int K = n_split ? p.block_cols : p.n_blocks * p.block_cols;
+    const int nkt = K / BK;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int g = lane >> 5, lr = lane & 31;
+    // Workgroups are handed to the 8 XCDs round-robin by linear id; give each XCD one
+    // contiguous range of the row-major tile order.
+    const int n_tiles = (N + BN - 1) / BN;
+    const int m_tiles = (p.T + BM - 1) / BM;
+    const int total_tiles = n_tiles * m_tiles;
+    const int per_xcd = (total_tiles + 7) / 8;
+    const int tile = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if ((int)(blockIdx.x >> 3) >= per_xcd || tile >= total_tiles) return;
+    const int tile_m = tile / n_tiles, tile_n = tile - tile_m * n_tiles;
+    const int m0 = tile_m * BM;
+    // N and the block widths are multiples of 32, so a wave's columns are all inside or all
+    // outside the matrix; a wave outside recomputes the first columns and its results are
+    // dropped by the column mask of the stores
+    const int nw_real = tile_n * BN + wave * 32;
+    const int nw = nw_real < N ? nw_real : 0;
+    int nblk = 0, nrow0 = nw;
+    if (n_split) {
+        nblk = nw / p.block_rows;
+        nrow0 = nw - nblk * p.block_rows;
+    }
+    const int tiles_per_kblock = n_split ? nkt : p.block_cols / BK;
+
+    float16v acc[RA];
+#pragma unroll
+    for (int i = 0; i < RA; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
+
+    // ---- A tile: lane l of a fetch instruction fills LDS slot (row l/8, chunk l%8) of its 8
+    //      rows with the chunk (l%8) ^ ((row/2)%8) of that row, so that the 16 rows that one
+    //      quarter of a fragment read touches (128-byte rows, two per 64-bank line) fall on
+    //      16 different bank groups; rows past T repeat row T-1 ----
+    const _Float16 *A = (const _Float16 *)p.A;
+    const _Float16 *src[FPW];
+#pragma unroll
+    for (int j = 0; j < FPW; ++j) {
+        int m = m0 + (wave + NW * j) * 8 + (lane >> 3);
+        m = m < p.T ? m : p.T - 1;
+        const int row = (wave + NW * j) * 8 + (lane >> 3);   // row inside the tile
+        src[j] = A + (int64_t)m * p.lda + (((lane & 7) ^ ((row >> 1) & 7)) * 8);
+    }
+    // The loads of the K loop are written as instructions rather than through the compiler:
+    // its own bookkeeping would wait for every outstanding fetch into LDS before the next LDS
+    // read, which is exactly the overlap this loop is built for.  The waits are in step().
+    const uint32_t lds_base = (uint32_t)(size_t)(lds_ptr *)smem_raw;
+    auto fetch_a = [&](int kt, int buf) {
+#pragma unroll
+        for (int j = 0; j < FPW; ++j) {
+            if (wave + NW * j < FETCHES) {
+                const _Float16 *gp = src[j] + kt * BK;
+                const uint32_t dst = lds_base + (uint32_t)((buf * STAGE + (wave + NW * j) * 8 * BK) * 2);
+                asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+                             :: "v"(gp), "s"(dst) : "memory", "m0");
+            }
+        }
+    };
+    // byte offset of this lane's fragment of k-step s inside row block 0 of a stage
+    int frag_off[4];
+#pragma unroll
+    for (int s = 0; s < 4; ++s) frag_off[s] = lr * (BK * 2) + (((g * 4 + s) ^ ((lr >> 1) & 7)) * 16);
+
+    auto frag_ptr = [&](int kt) -> const u32x4 * {
+        int blk, ktb, row;
+        if (n_split) {
+            blk = nblk; ktb = kt; row = nrow0;
+        } else {
+            blk = kt / tiles_per_kblock; ktb = kt - blk * tiles_per_kblock; row = nw;
+        }
+        const uint8_t *base = (const uint8_t *)blocks.b[blk].w;
+        return (const u32x4 *)(base + tiled_cell_offset(row >> 5, ktb, p.block_cols)) + lane;
+    };
+
+    // Three A stages and three sets of weight fragment registers: the loads of K tile t+2 are
+    // issued while tile t is multiplied.  The wait in front of the barrier is written by hand:
+    // it lets the loads of tile t+1 (4 fragment loads and this wave's share of the A fetches,
+    // issued after the fetches of tile t) stay in flight.
+    u32x4 bw[3][4];
+    int n_fetch = 0;   // A fetches this wave issues per stage
+#pragma unroll
+    for (int j = 0; j < FPW; ++j) n_fetch += (wave + NW * j < FETCHES) ? 1 : 0;
+    auto issue = [&](int kt, u32x4 (&dst)[4]) {
+        const u32x4 *q = frag_ptr(kt);
+        asm volatile("global_load_dwordx4 %0, %4, off\n\t"
+                     "global_load_dwordx4 %1, %4, off offset:1024\n\t"
+                     "global_load_dwordx4 %2, %4, off offset:2048\n\t"
+                     "global_load_dwordx4 %3, %4, off offset:3072"
+                     : "=&v"(dst[0]), "=&v"(dst[1]), "=&v"(dst[2]), "=&v"(dst[3]) : "v"(q) : "memory");
+        fetch_a(kt, kt % 3);
+    };
+#define STI_WAIT_LOADS(n) asm volatile("s_waitcnt vmcnt(" #n ")" ::: "memory")
+    auto step = [&](int kt, u32x4 (&bcur)[4], u32x4 (&bnew)[4]) {
+        // the weight fragments and the A stage of tile kt have landed (the barrier below is a
+        // scheduling boundary: no MFMA of this step is placed above the wait) ...
+        if (kt + 1 < nkt) {
+            if (n_fetch == 2) STI_WAIT_LOADS(6);
+            else if (n_fetch == 1) STI_WAIT_LOADS(5);
+            else STI_WAIT_LOADS(4);
+        } else {
+            STI_WAIT_LOADS(0);
+        }
+        // ... for every wave, and every wave is done reading the stage that is refilled next
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_sched_barrier(0);
+        if (kt + 2 < nkt) issue(kt + 2, bnew);
+        const unsigned char *stage = smem_raw + (kt % 3) * (STAGE * 2);
+        half8 a_cur[RA], a_nxt[RA];
+#pragma unroll
+        for (int i = 0; i < RA; ++i) a_cur[i] = *(const half8 *)(stage + i * (32 * BK * 2) + frag_off[0]);
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            if (s < 3) {
+#pragma unroll
+                for (int i = 0; i < RA; ++i)
+                    a_nxt[i] = *(const half8 *)(stage + i * (32 * BK * 2) + frag_off[s + 1]);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int i = 0; i < RA; ++i)
+                acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8, bcur[s]), a_cur[i],
+                                                              acc[i], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            if (s < 3) {
+#pragma unroll
+                for (int i = 0; i < RA; ++i) a_cur[i] = a_nxt[i];
+            }
+        }
+    };
+    static_assert(FPW <= 2, "the hand-written waits cover up to two A fetches per wave");
+    if (nkt > 0) issue(0, bw[0]);
+    if (nkt > 1) issue(1, bw[1]);
+    for (int kt = 0; kt < nkt; kt += 3) {
+        step(kt, bw[0], bw[2]);
+        if (kt + 1 < nkt) step(kt + 1, bw[1], bw[0]);
+        if (kt + 2 < nkt) step(kt + 2, bw[2], bw[1]);
+    }
+#undef STI_WAIT_LOADS
+
+    // ---- epilogue ----
+    // Lane l holds token row lr and output columns (v/4)*8 + g*4 + v%4 of each 32 x 32 block.
+    // Swapping the column groups 2q and 2q+1 between lanes l and l+32 leaves the lane with the
+    // 8 consecutive columns 16q + 8g .. +8 of its row: one 16-byte piece of the output row.
+    constexpr int LDT = BN + 8;   // padded row of the staged tile (halves): conflict-free 16-byte writes
+    _Float16 *tile_out = (_Float16 *)smem_raw;
+    const _Float16 *R = (const _Float16 *)p.resid;
+    f32x4 bias[2][2];
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+        const int c = 16 * q + 8 * g;     // first column of the piece inside the wave's strip
+        const float *bp;
+        if constexpr (KIND == GEMM_QKV) {
+            const int nrow = nrow0 + c;
+            const int which = nrow / p.d_head, e0 = nrow - which * p.d_head;
+            bp = (which == 0 ? p.bias0 : (which == 1 ? p.bias1 : p.bias2)) + blocks.b[nblk].shard * p.d_head + e0;
+        } else if constexpr (KIND == GEMM_FFN_UP) {
+            bp = p.bias0 + blocks.b[nblk].shard * p.block_rows + nrow0 + c;
+        } else {
+            bp = p.bias0 + nw + c;
+        }
+        bias[q][0] = *(const f32x4 *)bp;
+        bias[q][1] = *(const f32x4 *)(bp + 4);
+    }
+    __syncthreads();   // every wave is done with the A stages
+#pragma unroll
+    for (int i = 0; i < RA; ++i) {
+        const int row = i * 32 + lr;          // row inside the tile
+        half8 res[2];
+        if constexpr (!n_split) {
+            const int m = m0 + row;
+#pragma unroll
+            for (int q = 0; q < 2; ++q) {
+                u32x4 v = {0, 0, 0, 0};
+                if (m < p.T) v = *(const u32x4 *)(R + (int64_t)m * p.ldr + nw + 16 * q + 8 * g);
+                res[q] = __builtin_bit_cast(half8, v);
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            float x[8];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                // (element values first: a bit cast applied to a vector element itself reads element 0)
+                const float lo = acc[i][(2 * q) * 4 + e], hi = acc[i][(2 * q + 1) * 4 + e];
+                const auto sw = __builtin_amdgcn_permlane32_swap(__builtin_bit_cast(uint32_t, lo),
+                                                                 __builtin_bit_cast(uint32_t, hi), false, false);
+                const uint32_t s0 = sw[0], s1 = sw[1];
+                x[e] = __builtin_bit_cast(float, s0);
+                x[4 + e] = __builtin_bit_cast(float, s1);
+            }
+            half8 o;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                float y = x[e] + bias[q][e >> 2][e & 3];
+                if constexpr (KIND == GEMM_FFN_UP) y = gelu_erf(y);
+                if constexpr (!n_split) y += (float)res[q][e];
+                o[e] = (_Float16)y;
+            }
+            *(half8 *)(tile_out + row * LDT + wave * 32 + 16 * q + 8 * g) = o;
+        }
+    }
+    __syncthreads();
+    // BN/8 lanes per tile row: every store instruction writes whole rows of the tile
+    _Float16 *C = (_Float16 *)p.C;
+    constexpr int PIECES_PER_ROW = BN / 8;
+    constexpr int PASSES = BM * PIECES_PER_ROW / NT;
+    static_assert(PASSES * NT == BM * PIECES_PER_ROW, "whole passes");
+    u32x4 piece[PASSES];
+#pragma unroll
+    for (int j = 0; j < PASSES; ++j) {
+        const int pc = tid + NT * j;
+        piece[j] = *(const u32x4 *)(tile_out + (pc / PIECES_PER_ROW) * LDT + (pc % PIECES_PER_ROW) * 8);
+    }
+#pragma unroll
+    for (int j = 0; j < PASSES; ++j) {
+        const int pc = tid + NT * j;
+        const int m = m0 + pc / PIECES_PER_ROW, n = tile_n * BN + (pc % PIECES_PER_ROW) * 8;
+        if (m < p.T && n < N) *(u32x4 *)(C + (int64_t)m * p.ldc + n) = piece[j];
+    }
+}
+
+template <int KIND, int RA, int NW>
+hipError_t launch_shape(const GemmProblem &p, const GemmBlocks &blocks, int N, hipStream_t stream)
+{
+    constexpr int BM = RA * 32, BN = NW * 32;
+    constexpr size_t lds = wide_lds_bytes<RA, NW>();
+    static bool attr_set = false;   // per instantiation
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void *)gemm_wide_kernel<KIND, RA, NW>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const int total = ((N + BN - 1) / BN) * ((p.T + BM - 1) / BM);
+    dim3 grid(((total + 7) / 8) * 8);
+    gemm_wide_kernel<KIND, RA, NW><<<grid, dim3(NW * 64), lds, stream>>>(p, blocks);
+    return hipGetLastError();
+}
+
+template <int RA, int NW>
+hipError_t launch_kind(const GemmProblem &p, const GemmBlocks &blocks, int N, hipStream_t stream)
+{
+    switch (p.kind) {
+    case GEMM_QKV: return launch_shape<GEMM_QKV, RA, NW>(p, blocks, N, stream);
+    case GEMM_FFN_UP: return launch_shape<GEMM_FFN_UP, RA, NW>(p, blocks, N, stream);
+    case GEMM_OUT: return launch_shape<GEMM_OUT, RA, NW>(p, blocks, N, stream);
+    case GEMM_FFN_DOWN: return launch_shape<GEMM_FFN_DOWN, RA, NW>(p, blocks, N, stream);
+    }
+    return hipErrorInvalidValue;
+}
+
+struct Shape {
+    int ra, nw;
+};
+constexpr Shape kShapes[] = {{4, 12}, {4, 9}, {2, 12}, {2, 6}};
+constexpr int kComputeUnits = 256;
+constexpr int kWaveSlots = 12;   // waves a compute unit holds at this kernel's register budget
+
+}  // namespace
+
+// Tile shape for a [T x N] output: the one whose busiest compute unit has the least MFMA
+// work (workgroups are spread evenly over the units, floor(12 / NW) of them fit on one at a
+// time); ties go to fewer rounds of workgroups on that unit, then to more rows per weight
+// fragment, then to more waves per unit.
+bool gemm_wide_supported(const GemmProblem &p, const GemmBlocks &blocks)
+{
+    if (p.n_blocks <= 0 || p.T <= 0) return false;
+    for (int b = 0; b < p.n_blocks; ++b)
+        if (blocks.b[b].bits != kTiledBits) return false;
+    return true;
+}
+
+hipError_t launch_gemm_wide(const GemmProblem &p, const GemmBlocks &blocks, hipStream_t stream)
+{
+    const bool n_split = (p.kind == GEMM_QKV || p.kind == GEMM_FFN_UP);
+    const int N = n_split ? p.n_blocks * p.block_rows : p.block_rows;
+    if (p.T <= 0 || N <= 0) return hipSuccess;
+    if (!gemm_wide_supported(p, blocks)) return hipErrorInvalidValue;
+    if (N % 32 || p.block_rows % 32 || p.block_cols % BK || p.lda % 8 || p.ldc % 8) return hipErrorInvalidValue;
+    int best = -1;
+    long best_key[4] = {0, 0, 0, 0};
+    for (int c = 0; c < (int)(sizeof(kShapes) / sizeof(kShapes[0])); ++c) {
+        const int bm = kShapes[c].ra * 32, bn = kShapes[c].nw * 32;
+        const long tiles = (long)((N + bn - 1) / bn) * ((p.T + bm - 1) / bm);
+        const long per_cu = (tiles + kComputeUnits - 1) / kComputeUnits;        // workgroups on the busiest unit
+        const long resident = kWaveSlots / kShapes[c].nw;
+        const long key[4] = {per_cu * kShapes[c].nw * kShapes[c].ra,            // its MFMA work
+                             (per_cu + resident - 1) / resident,                // rounds
+                             -kShapes[c].ra,
+                             -(per_cu < resident ? per_cu : resident) * kShapes[c].nw};
+        bool better = best < 0;
+        for (int i = 0; i < 4 && !better; ++i) {
+            if (key[i] != best_key[i]) { better = key[i] < best_key[i]; break; }
+        }
+        if (better) {
+            best = c;
+            for (int i = 0; i < 4; ++i) best_key[i] = key[i];
+        }
+    }
+    switch (best) {
+    case 0: return launch_kind<4, 12>(p, blocks, N, stream);
+    case 1: return launch_kind<4, 9>(p, blocks, N, stream);
+    case 2: return launch_kind<2, 12>(p, blocks, N, stream);
+    default: return launch_kind<2, 6>(p, blocks, N, stream);
+    }
+}
+
+}  // namespace sti

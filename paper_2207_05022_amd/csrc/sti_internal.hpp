@@ -95,6 +95,10 @@ hipError_t launch_attention_f32(const float *qkv, float *ctx, int B, int L, int 
 // the fragment-tiled working buffer.  (The few-token variant below leaves float32 partial
 // sums instead, which launch_layernorm completes.)
 hipError_t launch_gemm_mfma(const GemmProblem &p, const GemmBlocks &blocks, hipStream_t stream);
+// gemm_wide.hip: the same projections when every block is a cell array of the fragment-tiled
+// binary16 working buffer (bits == kTiledBits); launch_gemm_mfma forwards such problems here.
+hipError_t launch_gemm_wide(const GemmProblem &p, const GemmBlocks &blocks, hipStream_t stream);
+bool gemm_wide_supported(const GemmProblem &p, const GemmBlocks &blocks);
 hipError_t launch_attention_mfma(const void *qkv, void *ctx, int B, int L, int m, int dh,
                                  hipStream_t stream);
 
