@@ -25,12 +25,12 @@ sys.path.insert(0, ROOT)
 # bench_config4_config1_hbm_counters.txt, calibrated against a 1 GiB device copy).  Reported
 # only while the kernel sources still hash to the value recorded with the counters.
 TRAFFIC = {
-    "gemm": {"files": ("gemm_mfma.hip", "weight_loader.hpp", "sti_internal.hpp"),
-             "sha256": "a56997602ed0535998b526fb379ce2182f87ecaaac962ce0fa9c1d44b8af2324",
-             "bytes_per_launch": 56852227},
+    "gemm": {"files": ("gemm_wide.hip", "weight_loader.hpp", "sti_internal.hpp"),
+             "sha256": "f4cb9125ed0d49f6f1393cf02fac762aab107f2a4342b00b45e88aa48791ccfc",
+             "bytes_per_launch": 56816464},
     "decode": {"files": ("decode.hip", "weight_loader.hpp", "sti_internal.hpp"),
-               "sha256": "22263b198e7902dd2f9d999ef21ef6b73e45ff75736a8d8697db7c44640daf38",
-               "bytes_per_launch": 6089423281},
+               "sha256": "b4097d48d2d6b2c311b2a94bb7e7c449fb68d529cb8ae8006718f0c12a7c7eb7",
+               "bytes_per_launch": 6089433727},
 }
 
 
@@ -76,7 +76,8 @@ def bench_model(P, D, torch, S, steps, warmup):
     store = P.binding.make_store(D.store_from_plan(shards))
     y = torch.empty_like(x)
     prec = P.STI_PREC_F16_MFMA
-    ws = torch.empty(P.sti_workspace_bytes(dims, wl.batch, wl.seq, prec), dtype=torch.uint8, device="cuda")
+    ws = torch.empty(P.sti_model_workspace_bytes(dims, wl.n_layers, wl.batch, wl.seq, prec), dtype=torch.uint8,
+                     device="cuda")
 
     def step():
         P.sti_model_forward(dims, store, params, wl.plan, x, y, prec, ws)
@@ -113,7 +114,7 @@ def bench_model(P, D, torch, S, steps, warmup):
         "ms_per_step": ms_per_step,
         "whole_path_tflops": total_flops / (ms_per_step * 1e-3) / 1e12,
         "roofline": {
-            "bound": "mfma", "kernel": "gemm_mfma_kernel (QKV, O, FFN1, FFN2 projections; weights from the per-layer binary16 working buffer)",
+            "bound": "mfma", "kernel": "gemm_wide_kernel (QKV, O, FFN1, FFN2 projections; weights from the binary16 working buffer)",
             "achieved": round(achieved_tflops, 2), "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s",
             "frac": round(achieved_tflops / MFMA_F16_PEAK_TFLOPS, 4), "traffic": measured_traffic("gemm"),
             "avg_launch_us": round(avg_launch_ms * 1e3, 2), "launches_per_step": launches_per_forward,

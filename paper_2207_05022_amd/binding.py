@@ -79,6 +79,8 @@ def _load():
             C.POINTER(StiDims), C.c_int, C.POINTER(StiShard), C.POINTER(StiLayerParams),
             C.POINTER(C.c_int8), C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int,
             C.c_void_p, C.c_size_t, C.c_void_p]
+    L.sti_model_workspace_bytes.restype = C.c_size_t
+    L.sti_model_workspace_bytes.argtypes = [C.POINTER(StiDims), C.c_int, C.c_int, C.c_int, C.c_int]
     L.sti_pipeline_staging_bytes.restype = C.c_size_t
     L.sti_pipeline_staging_bytes.argtypes = [C.POINTER(StiDims)]
     L.sti_pipeline_create.restype = C.c_int
@@ -177,6 +179,11 @@ def sti_decode_shards(shards: Sequence, weights_per_shard: int, out, workspace=N
 def sti_workspace_bytes(dims, batch: int, seq: int, precision: int) -> int:
     d = make_dims(dims)
     return int(lib.sti_workspace_bytes(C.byref(d), int(batch), int(seq), int(precision)))
+
+
+def sti_model_workspace_bytes(dims, n_layers: int, batch: int, seq: int, precision: int) -> int:
+    d = make_dims(dims)
+    return int(lib.sti_model_workspace_bytes(C.byref(d), int(n_layers), int(batch), int(seq), int(precision)))
 
 
 def sti_layer_forward(dims, shards: Sequence, params, x, y, precision: int, workspace,

@@ -173,9 +173,10 @@ sti_status check_decode_shard(const sti_shard &s)
 
 
 // Offsets of the scratch regions of one layer call (sized for all M shards present).
-WorkspaceLayout workspace_layout(const sti_dims &d, int64_t T, sti_precision prec)
+WorkspaceLayout workspace_layout(const sti_dims &d, int64_t T, sti_precision prec, int w16_layers)
 {
     WorkspaceLayout L;
+    L.w16_layers = (prec == STI_PREC_F32 || w16_layers < 1) ? 1 : w16_layers;
     const size_t es = (prec == STI_PREC_F32) ? 4 : 2;
     const size_t M = d.n_heads, dm = d.d_model, dh = d.d_head, f = d.ffn_per_shard;
     size_t off = 0;
@@ -185,7 +186,7 @@ WorkspaceLayout workspace_layout(const sti_dims &d, int64_t T, sti_precision pre
         return at;
     };
     if (prec == STI_PREC_F32) L.w32 = take(M * dm * (4 * dh + 2 * f) * 4);
-    else L.w16 = take(M * dm * (4 * dh + 2 * f) * 2);
+    else L.w16 = take((size_t)L.w16_layers * M * dm * (4 * dh + 2 * f) * 2);
     L.act[0] = take((size_t)T * dm * es);
     L.act[1] = take((size_t)T * dm * es);
     L.qkv = take((size_t)T * M * 3 * dh * es);
@@ -197,6 +198,7 @@ WorkspaceLayout workspace_layout(const sti_dims &d, int64_t T, sti_precision pre
     }
     L.h = take((size_t)T * dm * es);
     L.u = take((size_t)T * M * f * es);
+    if (L.w16_layers > 1) L.table = take((size_t)L.w16_layers * M * sizeof(ShardDesc));
     L.total = off;
     return L;
 }
@@ -257,7 +259,8 @@ constexpr int kWorkingBufferMinTokens = 512;
 // binary16 (MFMA precision); `out` is written as out_dtype.
 sti_status run_layer(const sti_dims &d, const sti_shard *shards, const sti_layer_params &prm,
                      const void *in, void *out, sti_dtype out_dtype, int B, int Lseq,
-                     sti_precision prec, uint8_t *ws, const WorkspaceLayout &wl, hipStream_t stream)
+                     sti_precision prec, uint8_t *ws, const WorkspaceLayout &wl, hipStream_t stream,
+                     const void *predecoded)
 {
     const int dm = d.d_model, M = d.n_heads, dh = d.d_head, f = d.ffn_per_shard;
     const int T = B * Lseq;
@@ -281,9 +284,10 @@ sti_status run_layer(const sti_dims &d, const sti_shard *shards, const sti_layer
         if (shards[present[p]].n_outliers > max_outliers) max_outliers = shards[present[p]].n_outliers;
     // shards with an outlier dictionary always go through the working buffer, where the
     // outliers are scattered back after the substitution pass
-    const bool predecode = !f32 && m > 0 && (T >= kWorkingBufferMinTokens || max_outliers > 0);
+    const bool predecode = !f32 && m > 0 && (predecoded || T >= kWorkingBufferMinTokens || max_outliers > 0);
     static_assert(kWorkingBufferMinTokens > kSkinnyMaxTokens, "the few-token GEMM decodes in registers");
-    if (predecode) {
+    const _Float16 *w16 = predecoded ? (const _Float16 *)predecoded : (const _Float16 *)(ws + wl.w16);
+    if (predecode && !predecoded) {
         InlineShardTable t;
         memset(&t, 0, sizeof(t));
         for (int p = 0; p < m; ++p) {
@@ -312,7 +316,7 @@ sti_status run_layer(const sti_dims &d, const sti_shard *shards, const sti_layer
             b1.b[p] = GemmBlock{w + off_1, nullptr, 32, present[p]};
             b2.b[p] = GemmBlock{w + off_2, nullptr, 32, present[p]};
         } else if (predecode) {
-            const _Float16 *w = (const _Float16 *)(ws + wl.w16) + (size_t)p * wsh;
+            const _Float16 *w = w16 + (size_t)p * wsh;
             bq.b[p] = GemmBlock{w, nullptr, 17, present[p]};
             bo.b[p] = GemmBlock{w + off_o, nullptr, 17, present[p]};
             b1.b[p] = GemmBlock{w + off_1, nullptr, 17, present[p]};
@@ -569,7 +573,14 @@ sti_status sti_model_forward(const sti_dims *dims, int n_layers, const sti_shard
             c = v;
         }
     }
-    const WorkspaceLayout wl = workspace_layout(*dims, T, precision);
+    // With room for every layer's working buffer (sti_model_workspace_bytes) the whole model is
+    // decompressed by one launch up front; otherwise each layer decompresses into the one
+    // buffer just before it runs.
+    WorkspaceLayout wl = workspace_layout(*dims, T, precision);
+    const bool whole_model_fits =
+        precision == STI_PREC_F16_MFMA && T >= kWorkingBufferMinTokens && n_layers > 1 &&
+        workspace_bytes >= workspace_layout(*dims, T, precision, n_layers).total;
+    if (whole_model_fits) wl = workspace_layout(*dims, T, precision, n_layers);
     if (!workspace || workspace_bytes < wl.total) return STI_ERR_WORKSPACE;
     if (!aligned(workspace, 256)) return STI_ERR_ALIGN;
     if (T == 0) return STI_OK;
@@ -580,6 +591,46 @@ sti_status sti_model_forward(const sti_dims *dims, int n_layers, const sti_shard
     if (n_layers == 0) {
         STI_TRY(hipMemcpyAsync(y, x, io_bytes, hipMemcpyDeviceToDevice, stream));
         return STI_OK;
+    }
+    const size_t wsh = (size_t)dims->d_model * (4 * (size_t)dims->d_head + 2 * (size_t)dims->ffn_per_shard);
+    std::vector<size_t> first_shard;   // index of a layer's first present shard in the model-wide table
+    if (whole_model_fits) {
+        std::vector<ShardDesc> table;
+        try {
+            first_shard.resize(n_layers);
+            table.reserve((size_t)n_layers * M);
+            for (int l = 0; l < n_layers; ++l) {
+                first_shard[l] = table.size();
+                for (int i = 0; i < M; ++i) {
+                    const sti_shard &s = chosen[(size_t)l * M + i];
+                    if (s.bitwidth != 0) table.push_back(make_desc(s, i));
+                }
+            }
+        } catch (const std::bad_alloc &) {
+            return STI_ERR_HIP;
+        }
+        if (!table.empty()) {
+            ShardDesc *dev_table = (ShardDesc *)(ws + wl.table);
+            STI_TRY(staging().upload(table.data(), table.size(), dev_table, stream));
+            STI_TRY(timed(STI_K_DECODE, stream, [&] {
+                return launch_decode_tiled_table(dev_table, (int)table.size(), dims->d_model, dims->d_head,
+                                                 dims->ffn_per_shard, ws + wl.w16, stream);
+            }));
+            // outlier dictionaries, layer by layer (absent in most stores)
+            for (int l = 0; l < n_layers; ++l) {
+                const size_t lo = first_shard[l], hi = (l + 1 < n_layers) ? first_shard[l + 1] : table.size();
+                uint32_t max_outliers = 0;
+                InlineShardTable t;
+                memset(&t, 0, sizeof(t));
+                for (size_t e = lo; e < hi; ++e) {
+                    t.d[e - lo] = table[e];
+                    if (table[e].n_outliers > max_outliers) max_outliers = table[e].n_outliers;
+                }
+                if (max_outliers > 0)
+                    STI_TRY(launch_patch_outliers_tiled(t, (int)(hi - lo), max_outliers, dims->d_model, dims->d_head,
+                                                        dims->ffn_per_shard, ws + wl.w16 + lo * wsh * 2, stream));
+            }
+        }
     }
     const sti_dtype act = (precision == STI_PREC_F32) ? STI_F32 : STI_F16;
     const void *cur = x;
@@ -592,13 +643,22 @@ sti_status sti_model_forward(const sti_dims *dims, int n_layers, const sti_shard
     for (int l = 0; l < n_layers; ++l) {
         const bool last = (l == n_layers - 1);
         void *out = last ? y : (void *)(ws + wl.act[next_buf]);
+        const void *predecoded = whole_model_fits ? (const void *)(ws + wl.w16 + first_shard[l] * wsh * 2) : nullptr;
         st = run_layer(*dims, &chosen[(size_t)l * M], params[l], cur, out, last ? io_dtype : act,
-                       batch, seq, precision, ws, wl, stream);
+                       batch, seq, precision, ws, wl, stream, predecoded);
         if (st != STI_OK) return st;
         cur = out;
         next_buf ^= 1;
     }
     return STI_OK;
+}
+
+size_t sti_model_workspace_bytes(const sti_dims *dims, int n_layers, int batch, int seq, sti_precision precision)
+{
+    if (check_dims(dims, batch, seq, precision) != STI_OK || n_layers < 0) return 0;
+    const int64_t T = (int64_t)batch * seq;
+    const bool whole_model = precision == STI_PREC_F16_MFMA && T >= kWorkingBufferMinTokens && n_layers > 1;
+    return workspace_layout(*dims, T, precision, whole_model ? n_layers : 1).total;
 }
 
 sti_status sti_profile_begin(void)

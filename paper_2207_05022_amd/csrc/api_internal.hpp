@@ -15,9 +15,12 @@ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 // Offsets of the scratch regions of one layer call inside the caller's workspace.
 struct WorkspaceLayout {
-    size_t w32 = 0, w16 = 0, act[2] = {0, 0}, qkv = 0, ctx = 0, pre = 0, h = 0, u = 0, total = 0;
+    size_t w32 = 0, w16 = 0, act[2] = {0, 0}, qkv = 0, ctx = 0, pre = 0, h = 0, u = 0, table = 0, total = 0;
+    int w16_layers = 1;   // layers the binary16 working buffer holds at once
 };
-WorkspaceLayout workspace_layout(const sti_dims &d, int64_t T, sti_precision prec);
+// w16_layers > 1: room for that many layers' binary16 working buffers (decompressed in one
+// launch by sti_model_forward) and for the device copy of their shard table.
+WorkspaceLayout workspace_layout(const sti_dims &d, int64_t T, sti_precision prec, int w16_layers = 1);
 
 sti_status check_dims(const sti_dims *dims, int batch, int seq, sti_precision prec);
 sti_status check_decode_shard(const sti_shard &s);   // bitwidth 2..6 or 32, pointers, alignment
@@ -28,6 +31,9 @@ sti_status check_io(const void *x, void *y, sti_dtype io, int64_t T, int d);
 // float32 (F32 precision) or binary16 (MFMA precision); `out` is written as out_dtype.
 sti_status run_layer(const sti_dims &d, const sti_shard *shards, const sti_layer_params &prm,
                      const void *in, void *out, sti_dtype out_dtype, int B, int Lseq,
-                     sti_precision prec, uint8_t *ws, const WorkspaceLayout &wl, hipStream_t stream);
+                     sti_precision prec, uint8_t *ws, const WorkspaceLayout &wl, hipStream_t stream,
+                     const void *predecoded = nullptr);
+// `predecoded`: the layer's present shards already sit there in fragment-tiled binary16 order
+// (outliers applied); run_layer then decompresses nothing.
 
 }  // namespace sti

@@ -237,7 +237,8 @@ hipError_t launch_decode(const ShardDesc *table, const InlineShardTable *inline_
 // ---------------------------------------------------------------------------
 namespace {
 
-__global__ __launch_bounds__(256) void decode_tiled_kernel(InlineShardTable tab, int total_cells,
+template <typename Table>
+__global__ __launch_bounds__(256) void decode_tiled_kernel(Table tab, int total_cells,
                                                            int d, int dh, int f, uint8_t *out)
 {
     __shared__ uint16_t lut[4][kLutEntries];
@@ -259,7 +260,7 @@ __global__ __launch_bounds__(256) void decode_tiled_kernel(InlineShardTable tab,
     else { c -= c_qkv + c_o + c_1; cols = f; sub_off = (int64_t)4 * dh * d + (int64_t)f * d; }
     const int tiles = cols >> 6;
     const int strip = c / tiles, kt = c - strip * tiles;
-    const ShardDesc sd = tab.d[p];
+    const ShardDesc sd = tab.get(p);
     const int bits = sd.bits;
     if (bits <= 6) {
         if (lane < (1 << bits)) lut[wave][lane] = (uint16_t)f16_bits(sd.codebook[lane]);
@@ -380,8 +381,20 @@ hipError_t launch_decode_tiled(const InlineShardTable &table, int n_shards, int 
     const int64_t cells = wsh / 2048 * n_shards;
     if (cells == 0) return hipSuccess;
     if (d % 64 || dh % 64 || f % 64 || cells > 0x7FFFFFF0) return hipErrorInvalidValue;
-    decode_tiled_kernel<<<dim3((uint32_t)((cells + 3) / 4)), dim3(256), 0, stream>>>(
-        table, (int)cells, d, dh, f, (uint8_t *)out);
+    decode_tiled_kernel<TableInline><<<dim3((uint32_t)((cells + 3) / 4)), dim3(256), 0, stream>>>(
+        TableInline{table}, (int)cells, d, dh, f, (uint8_t *)out);
+    return hipGetLastError();
+}
+
+hipError_t launch_decode_tiled_table(const ShardDesc *device_table, int n_shards, int d, int dh, int f,
+                                     void *out, hipStream_t stream)
+{
+    const int64_t wsh = (int64_t)d * (4 * dh + 2 * f);
+    const int64_t cells = wsh / 2048 * n_shards;
+    if (cells == 0) return hipSuccess;
+    if (d % 64 || dh % 64 || f % 64 || cells > 0x7FFFFFF0) return hipErrorInvalidValue;
+    decode_tiled_kernel<TablePtr><<<dim3((uint32_t)((cells + 3) / 4)), dim3(256), 0, stream>>>(
+        TablePtr{device_table}, (int)cells, d, dh, f, (uint8_t *)out);
     return hipGetLastError();
 }
 

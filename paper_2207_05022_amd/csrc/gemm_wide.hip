@@ -53,18 +53,24 @@ __device__ inline float gelu_erf(float z)
     return z * fmaf(zc, r, 0.5f);
 }
 
-template <int RA, int NW>
+template <int RA, int NW, int KS>
 constexpr size_t wide_lds_bytes()
 {
-    constexpr size_t stages = 3 * (size_t)(RA * 32) * BK * 2;
+    constexpr size_t stages = (size_t)KS * 3 * (RA * 32) * BK * 2;
     constexpr size_t tile = (size_t)(RA * 32) * (NW * 32 + 8) * 2;
-    return stages > tile ? stages : tile;
+    constexpr size_t partial = (size_t)(KS - 1) * (RA * 32) * (NW * 32) * 4;
+    constexpr size_t m = stages > tile ? stages : tile;
+    return m > partial ? m : partial;
 }
 
-template <int KIND, int RA, int NW>
-__global__ __launch_bounds__(NW * 64, 3) void gemm_wide_kernel(GemmProblem p, GemmBlocks blocks)
+// KS = 2 (outputs as narrow as d_model, long K): the workgroup has two groups of NW waves that
+// each take one half of K for the same tile, with A stages of their own; the second group
+// hands its accumulators over through LDS at the end.  Twice the waves per compute unit for
+// a tile count that is fixed by the output size.
+template <int KIND, int RA, int NW, int KS>
+__global__ __launch_bounds__(NW * KS * 64, 3) void gemm_wide_kernel(GemmProblem p, GemmBlocks blocks)
 {
-    constexpr int BM = RA * 32, BN = NW * 32, NT = NW * 64;
+    constexpr int BM = RA * 32, BN = NW * 32, NT = NW * KS * 64, NTH = NW * 64;
     constexpr bool n_split = (KIND == GEMM_QKV || KIND == GEMM_FFN_UP);
     constexpr int STAGE = BM * BK;              // halves per A stage
     constexpr int FETCHES = BM / 8;             // fetch instructions per A stage: 8 rows (1 KiB) each
@@ -74,9 +80,11 @@ __global__ __launch_bounds__(NW * 64, 3) void gemm_wide_kernel(GemmProblem p, Ge
 
     const int N = n_split ? p.n_blocks * p.block_rows : p.block_rows;
     const int K = n_split ? p.block_cols : p.n_blocks * p.block_cols;
-    const int nkt = K / BK;
+    const int nkt = K / BK / KS;           // K tiles of this wave's group
     const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wave_all = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int half = wave_all / NW, wave = wave_all - half * NW;   // K group, column strip
+    const int kt0 = half * nkt;
     const int g = lane >> 5, lr = lane & 31;
     // Workgroups are handed to the 8 XCDs round-robin by linear id; give each XCD one
     // contiguous range of the row-major tile order.
@@ -98,7 +106,7 @@ __global__ __launch_bounds__(NW * 64, 3) void gemm_wide_kernel(GemmProblem p, Ge
         nblk = nw / p.block_rows;
         nrow0 = nw - nblk * p.block_rows;
     }
-    const int tiles_per_kblock = n_split ? nkt : p.block_cols / BK;
+    const int tiles_per_kblock = n_split ? nkt * KS : p.block_cols / BK;
 
     float16v acc[RA];
 #pragma unroll
@@ -127,8 +135,8 @@ __global__ __launch_bounds__(NW * 64, 3) void gemm_wide_kernel(GemmProblem p, Ge
 #pragma unroll
         for (int j = 0; j < FPW; ++j) {
             if (wave + NW * j < FETCHES) {
-                const _Float16 *gp = src[j] + kt * BK;
-                const uint32_t dst = lds_base + (uint32_t)((buf * STAGE + (wave + NW * j) * 8 * BK) * 2);
+                const _Float16 *gp = src[j] + (kt0 + kt) * BK;
+                const uint32_t dst = lds_base + (uint32_t)(((half * 3 + buf) * STAGE + (wave + NW * j) * 8 * BK) * 2);
                 asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
                              :: "v"(gp), "s"(dst) : "memory", "m0");
             }
@@ -141,6 +149,7 @@ __global__ __launch_bounds__(NW * 64, 3) void gemm_wide_kernel(GemmProblem p, Ge
 
     auto frag_ptr = [&](int kt) -> const u32x4 * {
         int blk, ktb, row;
+        kt += kt0;
         if (n_split) {
             blk = nblk; ktb = kt; row = nrow0;
         } else {
@@ -183,7 +192,7 @@ __global__ __launch_bounds__(NW * 64, 3) void gemm_wide_kernel(GemmProblem p, Ge
         asm volatile("" ::: "memory");
         __builtin_amdgcn_sched_barrier(0);
         if (kt + 2 < nkt) issue(kt + 2, bnew);
-        const unsigned char *stage = smem_raw + (kt % 3) * (STAGE * 2);
+        const unsigned char *stage = smem_raw + (half * 3 + kt % 3) * (STAGE * 2);
         half8 a_cur[RA], a_nxt[RA];
 #pragma unroll
         for (int i = 0; i < RA; ++i) a_cur[i] = *(const half8 *)(stage + i * (32 * BK * 2) + frag_off[0]);
@@ -241,6 +250,26 @@ __global__ __launch_bounds__(NW * 64, 3) void gemm_wide_kernel(GemmProblem p, Ge
         bias[q][1] = *(const f32x4 *)(bp + 4);
     }
     __syncthreads();   // every wave is done with the A stages
+    if constexpr (KS == 2) {
+        // second K group -> LDS -> first K group (same lane, same registers)
+        float *part = (float *)smem_raw;
+        const int th = tid - half * NTH;
+        if (half == 1) {
+#pragma unroll
+            for (int i = 0; i < RA; ++i)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) part[(i * 16 + v) * NTH + th] = acc[i][v];
+        }
+        __syncthreads();
+        if (half == 0) {
+#pragma unroll
+            for (int i = 0; i < RA; ++i)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[i][v] += part[(i * 16 + v) * NTH + th];
+        }
+        __syncthreads();   // the sums are in registers: the buffer can take the staged tile
+    }
+    if (half == 0) {
 #pragma unroll
     for (int i = 0; i < RA; ++i) {
         const int row = i * 32 + lr;          // row inside the tile
@@ -278,6 +307,7 @@ __global__ __launch_bounds__(NW * 64, 3) void gemm_wide_kernel(GemmProblem p, Ge
             *(half8 *)(tile_out + row * LDT + wave * 32 + 16 * q + 8 * g) = o;
         }
     }
+    }
     __syncthreads();
     // BN/8 lanes per tile row: every store instruction writes whole rows of the tile
     _Float16 *C = (_Float16 *)p.C;
@@ -298,21 +328,21 @@ __global__ __launch_bounds__(NW * 64, 3) void gemm_wide_kernel(GemmProblem p, Ge
     }
 }
 
-template <int KIND, int RA, int NW>
+template <int KIND, int RA, int NW, int KS>
 hipError_t launch_shape(const GemmProblem &p, const GemmBlocks &blocks, int N, hipStream_t stream)
 {
     constexpr int BM = RA * 32, BN = NW * 32;
-    constexpr size_t lds = wide_lds_bytes<RA, NW>();
+    constexpr size_t lds = wide_lds_bytes<RA, NW, KS>();
     static bool attr_set = false;   // per instantiation
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)gemm_wide_kernel<KIND, RA, NW>,
+        hipError_t e = hipFuncSetAttribute((const void *)gemm_wide_kernel<KIND, RA, NW, KS>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     const int total = ((N + BN - 1) / BN) * ((p.T + BM - 1) / BM);
     dim3 grid(((total + 7) / 8) * 8);
-    gemm_wide_kernel<KIND, RA, NW><<<grid, dim3(NW * 64), lds, stream>>>(p, blocks);
+    gemm_wide_kernel<KIND, RA, NW, KS><<<grid, dim3(NW * KS * 64), lds, stream>>>(p, blocks);
     return hipGetLastError();
 }
 
@@ -320,10 +350,10 @@ template <int RA, int NW>
 hipError_t launch_kind(const GemmProblem &p, const GemmBlocks &blocks, int N, hipStream_t stream)
 {
     switch (p.kind) {
-    case GEMM_QKV: return launch_shape<GEMM_QKV, RA, NW>(p, blocks, N, stream);
-    case GEMM_FFN_UP: return launch_shape<GEMM_FFN_UP, RA, NW>(p, blocks, N, stream);
-    case GEMM_OUT: return launch_shape<GEMM_OUT, RA, NW>(p, blocks, N, stream);
-    case GEMM_FFN_DOWN: return launch_shape<GEMM_FFN_DOWN, RA, NW>(p, blocks, N, stream);
+    case GEMM_QKV: return launch_shape<GEMM_QKV, RA, NW, 1>(p, blocks, N, stream);
+    case GEMM_FFN_UP: return launch_shape<GEMM_FFN_UP, RA, NW, 1>(p, blocks, N, stream);
+    case GEMM_OUT: return launch_shape<GEMM_OUT, RA, NW, 1>(p, blocks, N, stream);
+    case GEMM_FFN_DOWN: return launch_shape<GEMM_FFN_DOWN, RA, NW, 1>(p, blocks, N, stream);
     }
     return hipErrorInvalidValue;
 }
@@ -375,6 +405,13 @@ hipError_t launch_gemm_wide(const GemmProblem &p, const GemmBlocks &blocks, hipS
             best = c;
             for (int i = 0; i < 4; ++i) best_key[i] = key[i];
         }
+    }
+    const int nkt_total = (n_split ? p.block_cols : p.n_blocks * p.block_cols) / BK;
+    if (!n_split && kShapes[best].ra == 2 && kShapes[best].nw == 6 && best_key[1] == 1 &&
+        best_key[0] == 12 && nkt_total % 2 == 0 && nkt_total >= 4) {
+        // one 6-wave workgroup per unit: split K inside the workgroup to fill the unit
+        return p.kind == GEMM_OUT ? launch_shape<GEMM_OUT, 2, 6, 2>(p, blocks, N, stream)
+                                  : launch_shape<GEMM_FFN_DOWN, 2, 6, 2>(p, blocks, N, stream);
     }
     switch (best) {
     case 0: return launch_kind<4, 12>(p, blocks, N, stream);

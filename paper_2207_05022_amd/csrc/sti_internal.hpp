@@ -45,6 +45,10 @@ hipError_t launch_patch_outliers_tiled(const InlineShardTable &table, int n_shar
 // working buffer out[n_shards][Wsh] used by the matrix-core GEMM (see weight_loader.hpp).
 hipError_t launch_decode_tiled(const InlineShardTable &table, int n_shards, int d, int dh, int f,
                                void *out, hipStream_t stream);
+// Same with the table in device memory (any number of shards, e.g. every layer of a model in
+// one launch): shard p is written at out + p * Wsh * 2 bytes.
+hipError_t launch_decode_tiled_table(const ShardDesc *device_table, int n_shards, int d, int dh, int f,
+                                     void *out, hipStream_t stream);
 
 // ---- layer kernels ----------------------------------------------------------
 // The four projections of a layer over its present shards, seen as GEMMs

@@ -85,6 +85,15 @@ class Dims:
         self.d_model, self.n_heads, self.d_head, self.ffn_per_shard, self.ln_eps = d, M, dh, f, eps
 
 
+def test_model_workspace_query(P):
+    one = P.sti_workspace_bytes(Dims(), 32, 128, P.STI_PREC_F16_MFMA)
+    whole = P.sti_model_workspace_bytes(Dims(), 12, 32, 128, P.STI_PREC_F16_MFMA)
+    assert whole >= one + 11 * 12 * 589824 * 2            # eleven more binary16 working buffers
+    assert P.sti_model_workspace_bytes(Dims(), 1, 32, 128, P.STI_PREC_F16_MFMA) == one
+    assert P.sti_model_workspace_bytes(Dims(), 12, 32, 128, P.STI_PREC_F32) == P.sti_workspace_bytes(Dims(), 32, 128, P.STI_PREC_F32)
+    assert P.sti_model_workspace_bytes(Dims(), -1, 32, 128, P.STI_PREC_F16_MFMA) == 0
+
+
 def test_workspace_query(P):
     assert P.sti_workspace_bytes(Dims(), 1, 128, P.STI_PREC_F32) > 12 * 589824 * 4
     assert P.sti_workspace_bytes(Dims(), 32, 128, P.STI_PREC_F16_MFMA) > 0

@@ -238,3 +238,30 @@ def test_layers_apply_outlier_dictionaries(gpu, oracle_mod, prec, B, L):
     assert rel_err(without, want) > 3 * TOL[prec]     # the dictionaries matter at this tolerance
     got = run_gpu(gpu, wl, prec)
     assert rel_err(got, want) <= TOL[prec]
+
+
+def test_mfma_whole_model_decode_matches_per_layer_route(gpu, oracle_mod):
+    """With a workspace of sti_model_workspace_bytes all layers are decompressed by one launch;
+    the result must be the very bits of the per-layer route (same kernels, same order of
+    arithmetic) and within tolerance of the oracle; outlier dictionaries included."""
+    torch, P, D = gpu
+    wl = S.small_workload(777, MID, 4, 5, 128, n_absent=1, bit_choices=(2, 3, 4, 5, 6, 32), io_dtype="f16")
+    wl = _with_outliers(wl, 3, fraction=0.01)
+    prec = P.STI_PREC_F16_MFMA
+    shards, params, xd = D.upload_workload(wl)
+    store = P.make_store(D.store_from_plan(shards))
+    small = P.sti_workspace_bytes(wl.dims, 5, 128, prec)
+    big = P.sti_model_workspace_bytes(wl.dims, wl.n_layers, 5, 128, prec)
+    assert big > small
+    outs = []
+    for nbytes in (small, big):
+        ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+        y = torch.full_like(xd, float("nan"))
+        P.sti_model_forward(wl.dims, store, params, wl.plan, xd, y, prec, ws)
+        torch.cuda.synchronize()
+        outs.append(y)
+    assert torch.equal(outs[0], outs[1])
+    want = oracle_mod.model_forward(wl.dims, wl.shards, wl.params, wl.x)
+    assert rel_err(outs[1].float().cpu().numpy(), want) <= TOL["mfma"]
+    # below 512 tokens the query falls back to the one-layer size
+    assert P.sti_model_workspace_bytes(wl.dims, wl.n_layers, 1, 128, prec) == P.sti_workspace_bytes(wl.dims, 1, 128, prec)
