@@ -255,6 +255,53 @@ sti_status sti_pipeline_forward(sti_pipeline *pipeline, int n_layers, const sti_
 sti_status sti_pipeline_destroy(sti_pipeline *pipeline);
 
 /* ---------------------------------------------------------------------------
+ * Two-stage planning (Section "Compute Planning", Section "IO Planning").  Host
+ * code only: HOST pointers, no device work, no stream.
+ *
+ * sti_plan_tables holds what the paper profiles once per device (Section
+ * "Prerequisite: Offline Profiling"): the delay of loading one shard per
+ * bitwidth and of decompressing + executing one layer of m shards (sentence
+ * length and clock are fixed by whoever fills the table).
+ *
+ * sti_plan_submodel: of all n x m submodels (n layers of m shards) whose
+ * computation meets the deadline, n * t_comp[m-1] <= deadline_s, the one with
+ * the most shards; of those with equally many, the deepest.  n = m = 0 when even
+ * 1 x 1 is too slow.
+ *
+ * sti_plan_bitwidths: fidelity versions for the submodel layers 0..n-1 x shards
+ * 0..m-1.  AIB(0) is the IO time that filled the preload buffer (the preloaded
+ * shards inside the submodel), AIB(k) = AIB(k-1) + t_comp[m-1]; a shard chosen at
+ * layer l is charged to the budgets of layer l and of all later layers, and a
+ * plan is valid while no budget is negative (Section "Accumulated IO Budgets").
+ * Preloaded shards keep their version.  Pass 1 gives all others the highest
+ * uniform bitwidth (2..6, 32) that is valid - 2 bits if none is, and then pass 2
+ * is skipped; pass 2 walks `importance` (most important first) and raises a
+ * shard to 32 bits whenever the budgets allow (Section "Selecting Optimal Shard
+ * Versions").
+ *
+ *  preloaded   HOST [n_layers*n_shards], may be NULL: bitwidth of the version the
+ *              preload buffer holds of shard (l, i), 0 = not held.
+ *  importance  HOST [n_layers*n_shards]: a permutation of the shard ids
+ *              l*n_shards + i (required when n > 0).
+ *  plan        HOST out [n_layers*n_shards]: bitwidth, 0 = not in the submodel;
+ *              the layout sti_model_forward and sti_pipeline_forward take.
+ *  aib         HOST out [n], may be NULL: the budgets left after the allocation.
+ * Errors: STI_ERR_NULL, STI_ERR_DIMS (sizes, negative or non-finite delays,
+ * importance not a permutation), STI_ERR_BITWIDTH (preloaded).
+ * ------------------------------------------------------------------------- */
+typedef struct {
+    int32_t n_layers;      /* N: layers of the full model                              */
+    int32_t n_shards;      /* M: shards per layer                                      */
+    double t_io[6];        /* seconds to load one shard at 2, 3, 4, 5, 6, 32 bits      */
+    const double *t_comp;  /* HOST [n_shards]: t_comp[m-1] = seconds per layer of m shards */
+} sti_plan_tables;
+
+sti_status sti_plan_submodel(const sti_plan_tables *tables, double deadline_s, int32_t *n, int32_t *m);
+
+sti_status sti_plan_bitwidths(const sti_plan_tables *tables, int32_t n, int32_t m, const int8_t *preloaded,
+                              const int32_t *importance, int8_t *plan, double *aib);
+
+/* ---------------------------------------------------------------------------
  * Per-kernel timing (the counterpart of the paper's one-time hardware profiling
  * of computation delays, Section "Prerequisite: offline profiling").  Between
  * sti_profile_begin() and sti_profile_end() every kernel launch of the entry

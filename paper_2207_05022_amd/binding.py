@@ -48,6 +48,11 @@ class StiPipelineStats(C.Structure):
                 ("shards_preloaded", C.c_uint32)]
 
 
+class StiPlanTables(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("n_shards", C.c_int32), ("t_io", C.c_double * 6),
+                ("t_comp", C.POINTER(C.c_double))]
+
+
 class StiError(RuntimeError):
     def __init__(self, status: int, where: str):
         self.status = status
@@ -79,6 +84,11 @@ def _load():
             C.POINTER(StiDims), C.c_int, C.POINTER(StiShard), C.POINTER(StiLayerParams),
             C.POINTER(C.c_int8), C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int,
             C.c_void_p, C.c_size_t, C.c_void_p]
+    L.sti_plan_submodel.restype = C.c_int
+    L.sti_plan_submodel.argtypes = [C.POINTER(StiPlanTables), C.c_double, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
+    L.sti_plan_bitwidths.restype = C.c_int
+    L.sti_plan_bitwidths.argtypes = [C.POINTER(StiPlanTables), C.c_int32, C.c_int32, C.POINTER(C.c_int8),
+                                     C.POINTER(C.c_int32), C.POINTER(C.c_int8), C.POINTER(C.c_double)]
     L.sti_model_workspace_bytes.restype = C.c_size_t
     L.sti_model_workspace_bytes.argtypes = [C.POINTER(StiDims), C.c_int, C.c_int, C.c_int, C.c_int]
     L.sti_pipeline_staging_bytes.restype = C.c_size_t
@@ -307,3 +317,38 @@ class StiPipeline:
             self.close()
         except Exception:
             pass
+
+
+def _plan_tables(t_io, t_comp, n_layers: int):
+    tc = (C.c_double * len(t_comp))(*[float(x) for x in t_comp])
+    tab = StiPlanTables(int(n_layers), len(t_comp), (C.c_double * 6)(*[float(x) for x in t_io]), tc)
+    return tab, tc
+
+
+def sti_plan_submodel(t_io, t_comp, n_layers: int, deadline_s: float):
+    """t_io: 6 delays (bitwidths 2..6, 32); t_comp[m-1]: seconds per layer of m shards -> (n, m)."""
+    tab, _keep = _plan_tables(t_io, t_comp, n_layers)
+    n, m = C.c_int32(), C.c_int32()
+    st = lib.sti_plan_submodel(C.byref(tab), float(deadline_s), C.byref(n), C.byref(m))
+    if st != 0:
+        raise StiError(st, "sti_plan_submodel")
+    return int(n.value), int(m.value)
+
+
+def sti_plan_bitwidths(t_io, t_comp, n_layers: int, n: int, m: int, preloaded, importance):
+    """Returns (plan int8 [n_layers][M], aib float64 [n])."""
+    import numpy as np
+    tab, _keep = _plan_tables(t_io, t_comp, n_layers)
+    M = len(t_comp)
+    pre = None if preloaded is None else np.ascontiguousarray(preloaded, dtype=np.int8).ravel()
+    imp = np.ascontiguousarray(importance, dtype=np.int32).ravel()
+    plan = np.zeros(n_layers * M, dtype=np.int8)
+    aib = np.zeros(max(n, 1), dtype=np.float64)
+    st = lib.sti_plan_bitwidths(C.byref(tab), int(n), int(m),
+                                None if pre is None else pre.ctypes.data_as(C.POINTER(C.c_int8)),
+                                imp.ctypes.data_as(C.POINTER(C.c_int32)),
+                                plan.ctypes.data_as(C.POINTER(C.c_int8)),
+                                aib.ctypes.data_as(C.POINTER(C.c_double)))
+    if st != 0:
+        raise StiError(st, "sti_plan_bitwidths")
+    return plan.reshape(n_layers, M), aib[:n]
