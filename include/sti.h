@@ -302,6 +302,50 @@ sti_status sti_plan_bitwidths(const sti_plan_tables *tables, int32_t n, int32_t 
                               const int32_t *importance, int8_t *plan, double *aib);
 
 /* ---------------------------------------------------------------------------
+ * Quantizing a layer's shards into a k-bit version (Section "quantization per
+ * shard"; Section "Implementation", preprocessing of the model): one Gaussian is
+ * fitted to all weights of the layer (mean, biased variance + reg_covar); a weight
+ * whose log likelihood under it is below `loglik_threshold` (the paper: -4) is an
+ * outlier; the remaining weights are cut, in sorted order, into 2^k clusters of
+ * equal population, cluster c starting at rank floor(c*n/2^k); the centroid of a
+ * cluster is the arithmetic mean of its members; every weight is replaced by the
+ * k-bit index of the cluster whose value range holds it (all copies of a value go
+ * to one cluster; an outlier's placeholder follows the same rule) and outliers are
+ * bookkept per shard as (offset inside the shard, original value), offsets
+ * ascending.  The outputs are exactly what sti_shard takes: `packed` in the stream
+ * format above, one codebook shared by the layer's shards, outlier dictionaries.
+ *
+ *  weights        DEVICE float32 [n_heads][Wsh]: the layer's shards at full precision
+ *                 (the logical layout of Table 1), 16-byte aligned; Wsh % 1024 == 0
+ *                 (STI_ERR_UNSUPPORTED otherwise); finite values.
+ *  packed         DEVICE out [n_heads][Wsh*k/8] bytes.
+ *  codebook       DEVICE out float32 [2^k], ascending.
+ *  outlier_pos/val DEVICE out [n_heads][max_outliers_per_shard]; entries beyond a
+ *                 shard's count are left untouched.  outlier_count DEVICE out
+ *                 [n_heads]: the shard's number of outliers, which may exceed
+ *                 max_outliers_per_shard (then the dictionary is truncated: call
+ *                 again with more room).
+ *  stats          DEVICE out, may be NULL; status 1 = every weight is an outlier
+ *                 (nothing to cluster; packed and codebook are meaningless).
+ *  workspace      DEVICE, >= sti_quantize_workspace_bytes(dims), 256-byte aligned.
+ * Statistics are accumulated in float64 in a fixed order: a call is reproducible
+ * bit for bit.  Errors as for the other entry points.
+ * ------------------------------------------------------------------------- */
+typedef struct {
+    double mean;          /* fitted mean                                   */
+    double variance;      /* fitted variance (reg_covar included)          */
+    uint64_t n_outliers;  /* over all shards of the layer                  */
+    uint32_t status;      /* 0 ok, 1 no inliers                            */
+} sti_quant_stats;
+
+size_t sti_quantize_workspace_bytes(const sti_dims *dims);
+
+sti_status sti_quantize_layer(const sti_dims *dims, const float *weights, int bitwidth, double loglik_threshold,
+                              double reg_covar, uint8_t *packed, float *codebook, uint32_t *outlier_pos,
+                              float *outlier_val, uint32_t max_outliers_per_shard, uint32_t *outlier_count,
+                              sti_quant_stats *stats, void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* ---------------------------------------------------------------------------
  * Per-kernel timing (the counterpart of the paper's one-time hardware profiling
  * of computation delays, Section "Prerequisite: offline profiling").  Between
  * sti_profile_begin() and sti_profile_end() every kernel launch of the entry

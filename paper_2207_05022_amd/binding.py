@@ -53,6 +53,10 @@ class StiPlanTables(C.Structure):
                 ("t_comp", C.POINTER(C.c_double))]
 
 
+class StiQuantStats(C.Structure):
+    _fields_ = [("mean", C.c_double), ("variance", C.c_double), ("n_outliers", C.c_uint64), ("status", C.c_uint32)]
+
+
 class StiError(RuntimeError):
     def __init__(self, status: int, where: str):
         self.status = status
@@ -84,6 +88,12 @@ def _load():
             C.POINTER(StiDims), C.c_int, C.POINTER(StiShard), C.POINTER(StiLayerParams),
             C.POINTER(C.c_int8), C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int,
             C.c_void_p, C.c_size_t, C.c_void_p]
+    L.sti_quantize_workspace_bytes.restype = C.c_size_t
+    L.sti_quantize_workspace_bytes.argtypes = [C.POINTER(StiDims)]
+    L.sti_quantize_layer.restype = C.c_int
+    L.sti_quantize_layer.argtypes = [C.POINTER(StiDims), C.c_void_p, C.c_int, C.c_double, C.c_double, C.c_void_p,
+                                     C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p,
+                                     C.c_void_p, C.c_size_t, C.c_void_p]
     L.sti_plan_submodel.restype = C.c_int
     L.sti_plan_submodel.argtypes = [C.POINTER(StiPlanTables), C.c_double, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
     L.sti_plan_bitwidths.restype = C.c_int
@@ -352,3 +362,24 @@ def sti_plan_bitwidths(t_io, t_comp, n_layers: int, n: int, m: int, preloaded, i
     if st != 0:
         raise StiError(st, "sti_plan_bitwidths")
     return plan.reshape(n_layers, M), aib[:n]
+
+
+def sti_quantize_workspace_bytes(dims) -> int:
+    d = make_dims(dims)
+    return int(lib.sti_quantize_workspace_bytes(C.byref(d)))
+
+
+def sti_quantize_layer(dims, weights, bitwidth: int, packed, codebook, outlier_pos, outlier_val, outlier_count,
+                       stats, workspace, loglik_threshold: float = -4.0, reg_covar: float = 1e-6, stream=None) -> None:
+    """weights: CUDA float32 [M][Wsh]; packed: CUDA uint8 [M][Wsh*k/8]; codebook: CUDA float32 [2^k];
+    outlier_pos (int32/uint32 bits) and outlier_val (float32): CUDA [M][max]; outlier_count: CUDA int32 [M];
+    stats: CUDA uint8 tensor of 32 bytes or None (layout StiQuantStats)."""
+    d = make_dims(dims)
+    max_out = 0 if outlier_pos is None else int(outlier_pos.shape[1])
+    st = lib.sti_quantize_layer(C.byref(d), _ptr(weights), int(bitwidth), float(loglik_threshold), float(reg_covar),
+                                _ptr(packed), _ptr(codebook), _ptr(outlier_pos), _ptr(outlier_val), max_out,
+                                _ptr(outlier_count), _ptr(stats), _ptr(workspace),
+                                0 if workspace is None else workspace.numel() * workspace.element_size(),
+                                _stream_handle(stream))
+    if st != 0:
+        raise StiError(st, "sti_quantize_layer")

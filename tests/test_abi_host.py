@@ -179,3 +179,21 @@ def test_pipeline_argument_errors(P):
     assert P.lib.sti_pipeline_forward(None, 0, None, None, None, None, None, 0, 0, 0, 0, None, 0, None,
                                       None) == 1
     assert P.lib.sti_pipeline_destroy(None) == 0
+
+
+def test_quantizer_argument_errors(P):
+    d = P.binding.make_dims(Dims(d=768, M=12, dh=64, f=256))
+    assert P.lib.sti_quantize_workspace_bytes(C.byref(d)) > 62 * 65536 * 4
+    odd = P.binding.make_dims(Dims(d=24, M=2, dh=8, f=8))       # Wsh = 1152: not a multiple of 1024
+    assert P.lib.sti_quantize_workspace_bytes(C.byref(odd)) == 0
+    q = P.lib.sti_quantize_layer
+    args = lambda dims=d, w=FAKE, k=4, thr=-4.0, reg=1e-6, packed=FAKE, cb=FAKE, pos=FAKE, val=FAKE, mx=8, cnt=FAKE, ws=FAKE, wsb=1 << 40: \
+        (C.byref(dims), w, k, thr, reg, packed, cb, pos, val, mx, cnt, None, ws, wsb, None)
+    assert q(*args(w=None)) == 1
+    assert q(*args(cnt=None)) == 1
+    assert q(*args(pos=None)) == 1
+    assert q(*args(k=7)) == 3 and q(*args(k=32)) == 3
+    assert q(*args(dims=odd)) == 9
+    assert q(*args(reg=-1.0)) == 2 and q(*args(thr=float("nan"))) == 2
+    assert q(*args(w=FAKE + 4)) == 5
+    assert q(*args(ws=None)) == 6 and q(*args(wsb=1024)) == 6
