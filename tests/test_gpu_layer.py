@@ -265,3 +265,18 @@ def test_mfma_whole_model_decode_matches_per_layer_route(gpu, oracle_mod):
     assert rel_err(outs[1].float().cpu().numpy(), want) <= TOL["mfma"]
     # below 512 tokens the query falls back to the one-layer size
     assert P.sti_model_workspace_bytes(wl.dims, wl.n_layers, 1, 128, prec) == P.sti_workspace_bytes(wl.dims, 1, 128, prec)
+
+
+WIDE = S.Dims(128, 12, 64, 64, 1e-12)
+
+
+@pytest.mark.parametrize("B,L,n_absent", [(15, 137, 0), (8, 512, 0), (4, 130, 9), (3, 171, 5)])
+def test_mfma_working_buffer_gemm_tile_shapes(gpu, oracle_mod, B, L, n_absent):
+    """Token counts and shard counts that make the working-buffer GEMM pick each of its tile
+    shapes (64 x 384 and 128 x 288 tiles for the Q/K/V projection, the two-group K split and
+    its fallback for an odd number of K tiles in the output projection), with ragged last
+    row tiles and column tiles that are not full."""
+    wl = S.small_workload(1000 + B * L, WIDE, 2, B, L, n_absent=n_absent, io_dtype="f16")
+    want = oracle_mod.model_forward(WIDE, wl.shards, wl.params, wl.x)
+    got = run_gpu(gpu, wl, "mfma")
+    assert rel_err(got, want) <= TOL["mfma"]
