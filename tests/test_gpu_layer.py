@@ -280,3 +280,36 @@ def test_mfma_working_buffer_gemm_tile_shapes(gpu, oracle_mod, B, L, n_absent):
     want = oracle_mod.model_forward(WIDE, wl.shards, wl.params, wl.x)
     got = run_gpu(gpu, wl, "mfma")
     assert rel_err(got, want) <= TOL["mfma"]
+
+
+def test_model_forward_can_be_stream_captured(gpu, oracle_mod):
+    """The few-token path enqueues kernels only (no copies, no fills, no host waits), so a
+    caller may capture it into a graph; replays, with eager calls between them, must give the
+    eager result every time."""
+    torch, P, D = gpu
+    wl = S.small_workload(888, MID, 3, 2, 100, n_absent=1, io_dtype="f16")
+    prec = P.STI_PREC_F16_MFMA
+    shards, params, x = D.upload_workload(wl)
+    store = P.make_store(D.store_from_plan(shards))
+    ws = torch.empty(P.sti_workspace_bytes(MID, 2, 100, prec), dtype=torch.uint8, device="cuda")
+    y_eager = torch.empty_like(x)
+    P.sti_model_forward(MID, store, params, wl.plan, x, y_eager, prec, ws)
+    torch.cuda.synchronize()
+    want = oracle_mod.model_forward(MID, wl.shards, wl.params, wl.x)
+    assert rel_err(y_eager.float().cpu().numpy(), want) <= TOL["mfma"]
+    y_graph = torch.full_like(x, float("nan"))
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            P.sti_model_forward(MID, store, params, wl.plan, x, y_graph, prec, ws)
+    torch.cuda.synchronize()
+    for _ in range(3):
+        y_graph.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(y_graph, y_eager)
+        scratch = torch.empty_like(x)
+        P.sti_model_forward(MID, store, params, wl.plan, x, scratch, prec, ws)   # eager work between replays
+        torch.cuda.synchronize()
+        assert torch.equal(scratch, y_eager)
