@@ -9,10 +9,12 @@
 // unit holds all its waves at once (12 wave slots at this register budget): all waves of a
 // unit then move through the K loop in step, share one copy of the A tile and finish together.
 //   - the A tile [BM x 64] goes global -> LDS directly (global_load_lds_dwordx4, no
-//     registers, no LDS store instructions), two stages; its 16-byte chunks are XOR-swizzled
+//     registers, no LDS store instructions), three stages; its 16-byte chunks are XOR-swizzled
 //     by row pair so that the unpadded rows read without bank conflicts;
-//   - a wave's weight fragments are contiguous 1 KiB loads from the working buffer, one K
-//     tile ahead, straight into registers;
+//   - a wave's weight fragments are contiguous 1 KiB loads from the working buffer, two K
+//     tiles ahead, straight into registers; both kinds of load address memory as a scalar
+//     base plus a 32-bit lane offset (measured 1.5 % faster end to end than 64-bit lane
+//     addresses);
 //   - the A fragments of k-step s+1 are read from LDS while the MFMAs of step s run;
 //   - the weight fragment is the first MFMA operand, so a lane's accumulators are runs of
 //     output columns of one token row; v_permlane32_swap merges them into 16-byte pieces,
@@ -119,13 +121,13 @@ __global__ __launch_bounds__(NW * KS * 64, 3) void gemm_wide_kernel(GemmProblem 
     //      quarter of a fragment read touches (128-byte rows, two per 64-bank line) fall on
     //      16 different bank groups; rows past T repeat row T-1 ----
     const _Float16 *A = (const _Float16 *)p.A;
-    const _Float16 *src[FPW];
+    uint32_t src[FPW];   // byte offset of this lane's chunk from the start of its K tile
 #pragma unroll
     for (int j = 0; j < FPW; ++j) {
         int m = m0 + (wave + NW * j) * 8 + (lane >> 3);
         m = m < p.T ? m : p.T - 1;
         const int row = (wave + NW * j) * 8 + (lane >> 3);   // row inside the tile
-        src[j] = A + (int64_t)m * p.lda + (((lane & 7) ^ ((row >> 1) & 7)) * 8);
+        src[j] = (uint32_t)(((int64_t)m * p.lda + (((lane & 7) ^ ((row >> 1) & 7)) * 8)) * 2);
     }
     // The loads of the K loop are written as instructions rather than through the compiler:
     // its own bookkeeping would wait for every outstanding fetch into LDS before the next LDS
@@ -135,10 +137,10 @@ __global__ __launch_bounds__(NW * KS * 64, 3) void gemm_wide_kernel(GemmProblem 
 #pragma unroll
         for (int j = 0; j < FPW; ++j) {
             if (wave + NW * j < FETCHES) {
-                const _Float16 *gp = src[j] + (kt0 + kt) * BK;
+                const _Float16 *gp = A + (kt0 + kt) * BK;   // scalar base, per-lane 32-bit offset
                 const uint32_t dst = lds_base + (uint32_t)(((half * 3 + buf) * STAGE + (wave + NW * j) * 8 * BK) * 2);
-                asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
-                             :: "v"(gp), "s"(dst) : "memory", "m0");
+                asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                             :: "v"(src[j]), "s"(gp), "s"(dst) : "memory", "m0");
             }
         }
     };
@@ -147,7 +149,8 @@ __global__ __launch_bounds__(NW * KS * 64, 3) void gemm_wide_kernel(GemmProblem 
 #pragma unroll
     for (int s = 0; s < 4; ++s) frag_off[s] = lr * (BK * 2) + (((g * 4 + s) ^ ((lr >> 1) & 7)) * 16);
 
-    auto frag_ptr = [&](int kt) -> const u32x4 * {
+    const uint32_t lane16 = lane * 16;
+    auto frag_ptr = [&](int kt) -> const uint8_t * {
         int blk, ktb, row;
         kt += kt0;
         if (n_split) {
@@ -156,25 +159,27 @@ __global__ __launch_bounds__(NW * KS * 64, 3) void gemm_wide_kernel(GemmProblem 
             blk = kt / tiles_per_kblock; ktb = kt - blk * tiles_per_kblock; row = nw;
         }
         const uint8_t *base = (const uint8_t *)blocks.b[blk].w;
-        return (const u32x4 *)(base + tiled_cell_offset(row >> 5, ktb, p.block_cols)) + lane;
+        return base + tiled_cell_offset(row >> 5, ktb, p.block_cols);   // wave-uniform
     };
 
     // Three A stages and three sets of weight fragment registers: the loads of K tile t+2 are
-    // issued while tile t is multiplied.  The wait in front of the barrier is written by hand:
-    // it lets the loads of tile t+1 (4 fragment loads and this wave's share of the A fetches,
-    // issued after the fetches of tile t) stay in flight.
+    // issued while tile t is multiplied (A fetches first, then the 4 fragment loads; with K
+    // unsplit behind the MFMAs of the first k-step, so that those start right after the
+    // barrier: measured 2 % faster end to end than issuing at the top, while the split-K
+    // shapes are faster with the issue at the top).  The wait in front of the barrier is
+    // written by hand: it lets the loads of tile t+1, the last ones issued, stay in flight.
     u32x4 bw[3][4];
     int n_fetch = 0;   // A fetches this wave issues per stage
 #pragma unroll
     for (int j = 0; j < FPW; ++j) n_fetch += (wave + NW * j < FETCHES) ? 1 : 0;
     auto issue = [&](int kt, u32x4 (&dst)[4]) {
-        const u32x4 *q = frag_ptr(kt);
-        asm volatile("global_load_dwordx4 %0, %4, off\n\t"
-                     "global_load_dwordx4 %1, %4, off offset:1024\n\t"
-                     "global_load_dwordx4 %2, %4, off offset:2048\n\t"
-                     "global_load_dwordx4 %3, %4, off offset:3072"
-                     : "=&v"(dst[0]), "=&v"(dst[1]), "=&v"(dst[2]), "=&v"(dst[3]) : "v"(q) : "memory");
         fetch_a(kt, kt % 3);
+        const uint8_t *q = frag_ptr(kt);
+        asm volatile("global_load_dwordx4 %0, %4, %5\n\t"
+                     "global_load_dwordx4 %1, %4, %5 offset:1024\n\t"
+                     "global_load_dwordx4 %2, %4, %5 offset:2048\n\t"
+                     "global_load_dwordx4 %3, %4, %5 offset:3072"
+                     : "=&v"(dst[0]), "=&v"(dst[1]), "=&v"(dst[2]), "=&v"(dst[3]) : "v"(lane16), "s"(q) : "memory");
     };
 #define STI_WAIT_LOADS(n) asm volatile("s_waitcnt vmcnt(" #n ")" ::: "memory")
     auto step = [&](int kt, u32x4 (&bcur)[4], u32x4 (&bnew)[4]) {
@@ -191,7 +196,7 @@ __global__ __launch_bounds__(NW * KS * 64, 3) void gemm_wide_kernel(GemmProblem 
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
         __builtin_amdgcn_sched_barrier(0);
-        if (kt + 2 < nkt) issue(kt + 2, bnew);
+        if (KS == 2 && kt + 2 < nkt) issue(kt + 2, bnew);
         const unsigned char *stage = smem_raw + (half * 3 + kt % 3) * (STAGE * 2);
         half8 a_cur[RA], a_nxt[RA];
 #pragma unroll
@@ -208,6 +213,8 @@ __global__ __launch_bounds__(NW * KS * 64, 3) void gemm_wide_kernel(GemmProblem 
             for (int i = 0; i < RA; ++i)
                 acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8, bcur[s]), a_cur[i],
                                                               acc[i], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            if (KS == 1 && s == 0 && kt + 2 < nkt) issue(kt + 2, bnew);
             __builtin_amdgcn_sched_barrier(0);
             if (s < 3) {
 #pragma unroll
@@ -376,6 +383,8 @@ bool gemm_wide_supported(const GemmProblem &p, const GemmBlocks &blocks)
     if (p.n_blocks <= 0 || p.T <= 0) return false;
     for (int b = 0; b < p.n_blocks; ++b)
         if (blocks.b[b].bits != kTiledBits) return false;
+    // the A fetches address rows with 32-bit byte offsets from a scalar base
+    if ((int64_t)p.T * p.lda * 2 >= ((int64_t)1 << 31)) return false;
     return true;
 }
 
