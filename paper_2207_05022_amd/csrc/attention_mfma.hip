@@ -42,32 +42,8 @@ __global__ __launch_bounds__(NW * 64) void attention_mfma_kernel(const _Float16 
     const int64_t ld = (int64_t)m * 3 * DH;
     const _Float16 *base = qkv + (int64_t)b * L * ld + (int64_t)p * 3 * DH;
 
-    // stage K (row-major) of this head; rows >= L are zero
-    for (int r = tid >> 3; r < Lp; r += NW * 8) {
-        const int c = (tid & 7) * 8;
-        u32x4 kv = {0, 0, 0, 0};
-        if (r < L) kv = *(const u32x4 *)(base + (int64_t)r * ld + DH + c);
-        *(u32x4 *)(Ks + (size_t)r * KPAD + c) = kv;
-    }
-    // stage V transposed: a lane takes two consecutive keys and 8 features, so that the 64
-    // lanes of one LDS store write consecutive dwords of one V^T row (no bank conflicts)
-    for (int item = tid; item < (Lp / 2) * 8; item += NW * 64) {
-        const int pair = item % (Lp / 2), c = (item / (Lp / 2)) * 8;
-        const int r0 = 2 * pair;
-        u32x4 v0 = {0, 0, 0, 0}, v1 = {0, 0, 0, 0};
-        if (r0 < L) v0 = *(const u32x4 *)(base + (int64_t)r0 * ld + 2 * DH + c);
-        if (r0 + 1 < L) v1 = *(const u32x4 *)(base + (int64_t)(r0 + 1) * ld + 2 * DH + c);
-        const uint32_t a[4] = {v0.x, v0.y, v0.z, v0.w}, bq[4] = {v1.x, v1.y, v1.z, v1.w};
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const uint32_t lo = (a[i] & 0xFFFFu) | (bq[i] << 16);          // feature c + 2i
-            const uint32_t hi = (a[i] >> 16) | (bq[i] & 0xFFFF0000u);      // feature c + 2i + 1
-            *(uint32_t *)(Vt + (size_t)(c + 2 * i) * vts + r0) = lo;
-            *(uint32_t *)(Vt + (size_t)(c + 2 * i + 1) * vts + r0) = hi;
-        }
-    }
-
-    // this lane's query row as the B operand of S^T = K Q^T
+    // this lane's query row as the B operand of S^T = K Q^T (asked for first: the loads below
+    // and these share one round trip to memory)
     const int q = blockIdx.x * QB + wave * 32 + lr;
     half8 qf[4];
 #pragma unroll
@@ -75,6 +51,55 @@ __global__ __launch_bounds__(NW * 64) void attention_mfma_kernel(const _Float16 
         u32x4 v = {0, 0, 0, 0};
         if (q < L) v = *(const u32x4 *)(base + (int64_t)q * ld + s * 16 + g * 8);
         qf[s] = __builtin_bit_cast(half8, v);
+    }
+
+    // Stage K (row-major; rows >= L are zero) and V transposed, 128 keys per pass: all loads
+    // of a pass are issued before the first LDS store, so a pass costs one round trip.
+    //   K: a thread takes 16 bytes of rows tid/8 + 8 NW j;
+    //   V: a lane takes two consecutive keys and 8 features, so that the 64 lanes of one LDS
+    //      store write consecutive dwords of one V^T row (no bank conflicts).
+    constexpr int KJ = 16 / NW;           // K rows per thread and pass
+    constexpr int VJ = 8 / NW;            // V key pairs per thread and pass
+    const int kc = (tid & 7) * 8;
+    const int v_items = (Lp / 2) * 8;
+    for (int r0p = 0; r0p < Lp; r0p += 128) {
+        u32x4 kreg[KJ], v0[VJ], v1[VJ];
+#pragma unroll
+        for (int j = 0; j < KJ; ++j) {
+            const int r = r0p + (tid >> 3) + NW * 8 * j;
+            kreg[j] = u32x4{0, 0, 0, 0};
+            if (r < L) kreg[j] = *(const u32x4 *)(base + (int64_t)r * ld + DH + kc);
+        }
+#pragma unroll
+        for (int j = 0; j < VJ; ++j) {
+            const int item = (r0p / 128) * (NW * 64 * VJ) + tid + NW * 64 * j;
+            const int pair = item % (Lp / 2), c = (item / (Lp / 2)) * 8;
+            const int r0 = 2 * pair;
+            v0[j] = u32x4{0, 0, 0, 0};
+            v1[j] = u32x4{0, 0, 0, 0};
+            if (item < v_items && r0 < L) v0[j] = *(const u32x4 *)(base + (int64_t)r0 * ld + 2 * DH + c);
+            if (item < v_items && r0 + 1 < L) v1[j] = *(const u32x4 *)(base + (int64_t)(r0 + 1) * ld + 2 * DH + c);
+        }
+#pragma unroll
+        for (int j = 0; j < KJ; ++j) {
+            const int r = r0p + (tid >> 3) + NW * 8 * j;
+            if (r < Lp) *(u32x4 *)(Ks + (size_t)r * KPAD + kc) = kreg[j];
+        }
+#pragma unroll
+        for (int j = 0; j < VJ; ++j) {
+            const int item = (r0p / 128) * (NW * 64 * VJ) + tid + NW * 64 * j;
+            if (item >= v_items) continue;
+            const int pair = item % (Lp / 2), c = (item / (Lp / 2)) * 8;
+            const int r0 = 2 * pair;
+            const uint32_t a[4] = {v0[j].x, v0[j].y, v0[j].z, v0[j].w}, bq[4] = {v1[j].x, v1[j].y, v1[j].z, v1[j].w};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const uint32_t lo = (a[i] & 0xFFFFu) | (bq[i] << 16);          // feature c + 2i
+                const uint32_t hi = (a[i] >> 16) | (bq[i] & 0xFFFF0000u);      // feature c + 2i + 1
+                *(uint32_t *)(Vt + (size_t)(c + 2 * i) * vts + r0) = lo;
+                *(uint32_t *)(Vt + (size_t)(c + 2 * i + 1) * vts + r0) = hi;
+            }
+        }
     }
     __syncthreads();
 
