@@ -27,7 +27,9 @@ constexpr int KPAD = DH + 8;   // padded K row (halves)
 __device__ inline int vt_stride(int Lp) { return Lp + 8; }
 
 // NW waves per workgroup, 32 queries each.
-template <int NW>
+// SHORT (at most 128 keys): all scores stay in registers, the row maximum is known before the
+// first exponential, and the output accumulators are never rescaled.
+template <int NW, bool SHORT>
 __global__ __launch_bounds__(NW * 64) void attention_mfma_kernel(const _Float16 *qkv, _Float16 *ctx,
                                                                  int L, int Lp, int m)
 {
@@ -112,6 +114,64 @@ __global__ __launch_bounds__(NW * 64) void attention_mfma_kernel(const _Float16 
         for (int v = 0; v < 16; ++v) o[e][v] = 0.f;
 
     const int nkb = Lp / 32;
+    // O^T += V^T P^T over the two k16 steps of key block kb; pk = the block's probabilities
+    auto add_pv = [&](int kb, const uint32_t (&pk)[8]) {
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2) {
+            u32x4 pv = {pk[4 * s2], pk[4 * s2 + 1], pk[4 * s2 + 2], pk[4 * s2 + 3]};
+            half8 pf = __builtin_bit_cast(half8, pv);
+            const int key0 = kb * 32 + (2 * s2) * 8 + g * 4;
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {
+                const _Float16 *vrow = Vt + (size_t)(e * 32 + lr) * vts + key0;
+                u32x2 lo = *(const u32x2 *)vrow;
+                u32x2 hi = *(const u32x2 *)(vrow + 8);
+                u32x4 vv = {lo.x, lo.y, hi.x, hi.y};
+                o[e] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8, vv), pf,
+                                                              o[e], 0, 0, 0);
+            }
+        }
+    };
+    if constexpr (SHORT) {
+        float16v sc[4];
+        float mx = -INFINITY;
+#pragma unroll
+        for (int kb = 0; kb < 4; ++kb) {
+            if (kb >= nkb) break;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) sc[kb][v] = 0.f;
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                half8 kf = *(const half8 *)(Ks + (size_t)(kb * 32 + lr) * KPAD + s * 16 + g * 8);
+                sc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf, qf[s], sc[kb], 0, 0, 0);
+            }
+            if (kb * 32 + 32 > L) {   // keys past L sit in the last block only
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int key = kb * 32 + (v >> 2) * 8 + g * 4 + (v & 3);
+                    sc[kb][v] = (key < L) ? sc[kb][v] : -INFINITY;
+                }
+            }
+#pragma unroll
+            for (int v = 0; v < 16; ++v) mx = fmaxf(mx, sc[kb][v]);
+        }
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        const float shift = -mx * scale;   // (scale > 0: the maximum of the scaled scores)
+#pragma unroll
+        for (int kb = 0; kb < 4; ++kb) {
+            if (kb >= nkb) break;
+            uint32_t pk[8];
+#pragma unroll
+            for (int v = 0; v < 16; v += 2) {
+                const float p0 = __builtin_amdgcn_exp2f(fmaf(sc[kb][v], scale, shift));
+                const float p1 = __builtin_amdgcn_exp2f(fmaf(sc[kb][v + 1], scale, shift));
+                run_sum += p0 + p1;
+                pk[v / 2] = (uint32_t)__builtin_bit_cast(uint16_t, (_Float16)p0) |
+                            ((uint32_t)__builtin_bit_cast(uint16_t, (_Float16)p1) << 16);
+            }
+            add_pv(kb, pk);
+        }
+    } else
     for (int kb = 0; kb < nkb; ++kb) {
         float16v s_acc;
 #pragma unroll
@@ -150,22 +210,7 @@ __global__ __launch_bounds__(NW * 64) void attention_mfma_kernel(const _Float16 
         for (int e = 0; e < 2; ++e)
 #pragma unroll
             for (int v = 0; v < 16; ++v) o[e][v] *= alpha;
-        // O^T += V^T P^T over the two k16 steps of this key block
-#pragma unroll
-        for (int s2 = 0; s2 < 2; ++s2) {
-            u32x4 pv = {pk[4 * s2], pk[4 * s2 + 1], pk[4 * s2 + 2], pk[4 * s2 + 3]};
-            half8 pf = __builtin_bit_cast(half8, pv);
-            const int key0 = kb * 32 + (2 * s2) * 8 + g * 4;
-#pragma unroll
-            for (int e = 0; e < 2; ++e) {
-                const _Float16 *vrow = Vt + (size_t)(e * 32 + lr) * vts + key0;
-                u32x2 lo = *(const u32x2 *)vrow;
-                u32x2 hi = *(const u32x2 *)(vrow + 8);
-                u32x4 vv = {lo.x, lo.y, hi.x, hi.y};
-                o[e] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8, vv), pf,
-                                                              o[e], 0, 0, 0);
-            }
-        }
+        add_pv(kb, pk);
     }
     run_sum += __shfl_xor(run_sum, 32, 64);
     if (q >= L) return;
@@ -193,10 +238,10 @@ hipError_t launch_attention_mfma(const void *qkv, void *ctx, int B, int L, int m
     const size_t lds = ((size_t)Lp * KPAD + (size_t)DH * (Lp + 8)) * sizeof(_Float16);
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)attention_mfma_kernel<4>,
+        hipError_t e = hipFuncSetAttribute((const void *)attention_mfma_kernel<4, false>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e == hipSuccess)
-            e = hipFuncSetAttribute((const void *)attention_mfma_kernel<2>,
+            e = hipFuncSetAttribute((const void *)attention_mfma_kernel<2, false>,
                                     hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
         attr_set = true;
@@ -205,12 +250,20 @@ hipError_t launch_attention_mfma(const void *qkv, void *ctx, int B, int L, int m
     const bool small_wg = (int64_t)B * m * ((L + 127) / 128) < 128 && L > 32;
     if (small_wg) {
         dim3 grid((L + 63) / 64, m, B);
-        attention_mfma_kernel<2><<<grid, dim3(128), lds, stream>>>((const _Float16 *)qkv,
-                                                                   (_Float16 *)ctx, L, Lp, m);
+        if (Lp <= 128)
+            attention_mfma_kernel<2, true><<<grid, dim3(128), lds, stream>>>((const _Float16 *)qkv,
+                                                                             (_Float16 *)ctx, L, Lp, m);
+        else
+            attention_mfma_kernel<2, false><<<grid, dim3(128), lds, stream>>>((const _Float16 *)qkv,
+                                                                              (_Float16 *)ctx, L, Lp, m);
     } else {
         dim3 grid((L + 127) / 128, m, B);
-        attention_mfma_kernel<4><<<grid, dim3(256), lds, stream>>>((const _Float16 *)qkv,
-                                                                   (_Float16 *)ctx, L, Lp, m);
+        if (Lp <= 128)
+            attention_mfma_kernel<4, true><<<grid, dim3(256), lds, stream>>>((const _Float16 *)qkv,
+                                                                             (_Float16 *)ctx, L, Lp, m);
+        else
+            attention_mfma_kernel<4, false><<<grid, dim3(256), lds, stream>>>((const _Float16 *)qkv,
+                                                                              (_Float16 *)ctx, L, Lp, m);
     }
     return hipGetLastError();
 }
