@@ -30,7 +30,7 @@ __device__ inline int vt_stride(int Lp) { return Lp + 8; }
 // SHORT (at most 128 keys): all scores stay in registers, the row maximum is known before the
 // first exponential, and the output accumulators are never rescaled.
 template <int NW, bool SHORT>
-__global__ __launch_bounds__(NW * 64) void attention_mfma_kernel(const _Float16 *qkv, _Float16 *ctx,
+__global__ __launch_bounds__(NW * 64, 2) void attention_mfma_kernel(const _Float16 *qkv, _Float16 *ctx,
                                                                  int L, int Lp, int m)
 {
     constexpr int QB = NW * 32;
