@@ -196,6 +196,62 @@ def bench_host_link(P, D, torch, S, steps, warmup):
     return out
 
 
+def bench_few_token(P, D, torch, S, steps, warmup):
+    """Configurations 0, 2 and 3 (one sequence of 128 / 128 / 256 tokens): the latency-bound
+    regime of single-input inference.  Resident shards, float32 in and out."""
+    out = {}
+    prec = P.STI_PREC_F16_MFMA
+    for name, make in (("config0", S.config0), ("config2", S.config2), ("config3", S.config3)):
+        wl = make()
+        shards, params, x = D.upload_workload(wl)
+        store = P.make_store(D.store_from_plan(shards))
+        y = torch.empty_like(x)
+        ws = torch.empty(P.sti_model_workspace_bytes(wl.dims, wl.n_layers, wl.batch, wl.seq, prec),
+                         dtype=torch.uint8, device="cuda")
+        run = lambda: P.sti_model_forward(wl.dims, store, params, wl.plan, x, y, prec, ws)
+        for _ in range(max(1, warmup)):
+            run()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            run()
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) / steps * 1e3
+        out[name] = {"tokens": wl.tokens, "layers": wl.n_layers, "ms_per_forward": round(ms, 4),
+                     "us_per_layer": round(ms * 1e3 / wl.n_layers, 2),
+                     "tokens_per_s": round(wl.tokens / ms * 1e3, 1)}
+    return out
+
+
+def bench_quantizer(P, torch, S, steps, warmup):
+    """Outlier-aware quantization of one BERT-base layer (12 shards of float32 weights
+    ~ N(0, 0.04^2)) into k-bit indexes + centroids + outlier lists, k = 2, 4, 6."""
+    dims = S.BERT_BASE
+    M, wsh = dims.n_heads, dims.weights_per_shard
+    gen = torch.Generator(device="cuda").manual_seed(220705022)
+    w = torch.randn(M, wsh, device="cuda", generator=gen) * 0.04
+    ws = torch.empty(P.sti_quantize_workspace_bytes(dims), dtype=torch.uint8, device="cuda")
+    out = {"workload": "one BERT-base layer, 12 shards x 589824 float32 weights"}
+    for k in (2, 4, 6):
+        packed = torch.empty(M, wsh * k // 8, dtype=torch.uint8, device="cuda")
+        cb = torch.empty(1 << k, device="cuda")
+        pos = torch.empty(M, 4096, dtype=torch.int32, device="cuda")
+        val = torch.empty(M, 4096, device="cuda")
+        cnt = torch.empty(M, dtype=torch.int32, device="cuda")
+        st = torch.zeros(32, dtype=torch.uint8, device="cuda")
+        run = lambda: P.sti_quantize_layer(dims, w, k, packed, cb, pos, val, cnt, st, ws)
+        for _ in range(max(1, warmup)):
+            run()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            run()
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) / steps * 1e3
+        out[f"k{k}"] = {"ms_per_layer": round(ms, 4), "input_GBps": round(M * wsh * 4 / ms / 1e6, 1)}
+    return out
+
+
 def cpu_baselines(S, wl, ds):
     """The oracle as it stands, on a bounded sample of both workloads."""
     import oracle
@@ -230,6 +286,10 @@ def main():
     ap.add_argument("--host-link", action="store_true",
                     help="also time the load || compute pipeline with the shard streams in pinned host "
                          "memory (reported beside the headline value, never as it)")
+    ap.add_argument("--few-token", action="store_true",
+                    help="also time configurations 0, 2 and 3 (reported beside the headline value)")
+    ap.add_argument("--quantize", action="store_true",
+                    help="also time the outlier-aware quantizer on one BERT-base layer")
     args = ap.parse_args()
     if args.print_source_hashes:
         for k, t in TRAFFIC.items():
@@ -270,6 +330,10 @@ def main():
     }
     if args.host_link:
         line["host_link_pipeline"] = bench_host_link(P, D, torch, S, args.steps, args.warmup)
+    if args.few_token:
+        line["few_token"] = bench_few_token(P, D, torch, S, args.steps, args.warmup)
+    if args.quantize:
+        line["quantizer"] = bench_quantizer(P, torch, S, args.steps, args.warmup)
     if not args.no_cpu_baseline:
         cpu_model, cpu_dec = cpu_baselines(S, wl, ds)
         line["cpu_baseline"] = cpu_model
