@@ -573,9 +573,9 @@ sti_status sti_model_forward(const sti_dims *dims, int n_layers, const sti_shard
             c = v;
         }
     }
-    // With room for every layer's working buffer (sti_model_workspace_bytes) the whole model is
-    // decompressed by one launch up front; otherwise each layer decompresses into the one
-    // buffer just before it runs.
+    // With room for every layer's working buffer (sti_model_workspace_bytes) the model is
+    // decompressed a few layers per launch (below); otherwise each layer decompresses into the
+    // one buffer just before it runs.
     WorkspaceLayout wl = workspace_layout(*dims, T, precision);
     const bool whole_model_fits =
         precision == STI_PREC_F16_MFMA && T >= kWorkingBufferMinTokens && n_layers > 1 &&
@@ -594,8 +594,8 @@ sti_status sti_model_forward(const sti_dims *dims, int n_layers, const sti_shard
     }
     const size_t wsh = (size_t)dims->d_model * (4 * (size_t)dims->d_head + 2 * (size_t)dims->ffn_per_shard);
     std::vector<size_t> first_shard;   // index of a layer's first present shard in the model-wide table
+    std::vector<ShardDesc> table;
     if (whole_model_fits) {
-        std::vector<ShardDesc> table;
         try {
             first_shard.resize(n_layers);
             table.reserve((size_t)n_layers * M);
@@ -609,29 +609,42 @@ sti_status sti_model_forward(const sti_dims *dims, int n_layers, const sti_shard
         } catch (const std::bad_alloc &) {
             return STI_ERR_HIP;
         }
-        if (!table.empty()) {
-            ShardDesc *dev_table = (ShardDesc *)(ws + wl.table);
-            STI_TRY(staging().upload(table.data(), table.size(), dev_table, stream));
-            STI_TRY(timed(STI_K_DECODE, stream, [&] {
-                return launch_decode_tiled_table(dev_table, (int)table.size(), dims->d_model, dims->d_head,
-                                                 dims->ffn_per_shard, ws + wl.w16, stream);
-            }));
-            // outlier dictionaries, layer by layer (absent in most stores)
-            for (int l = 0; l < n_layers; ++l) {
-                const size_t lo = first_shard[l], hi = (l + 1 < n_layers) ? first_shard[l + 1] : table.size();
-                uint32_t max_outliers = 0;
-                InlineShardTable t;
-                memset(&t, 0, sizeof(t));
-                for (size_t e = lo; e < hi; ++e) {
-                    t.d[e - lo] = table[e];
-                    if (table[e].n_outliers > max_outliers) max_outliers = table[e].n_outliers;
-                }
-                if (max_outliers > 0)
-                    STI_TRY(launch_patch_outliers_tiled(t, (int)(hi - lo), max_outliers, dims->d_model, dims->d_head,
-                                                        dims->ffn_per_shard, ws + wl.w16 + lo * wsh * 2, stream));
-            }
-        }
+        if (!table.empty())
+            STI_TRY(staging().upload(table.data(), table.size(), (ShardDesc *)(ws + wl.table), stream));
     }
+    // Layers are decompressed in groups, each group right before its first layer: working
+    // buffers written shortly before they are read are still in the memory-side cache (the
+    // FFN2 projection measured 7 % faster than with one launch for the whole model up front),
+    // while one launch per layer is too short to keep HBM busy.  A group is as many layers as
+    // fit 64 MiB of working buffers (4 layers of BERT-base).
+    const size_t layer_w16_bytes = (size_t)M * wsh * 2;
+    int decode_group = (int)(((size_t)64 << 20) / (layer_w16_bytes ? layer_w16_bytes : 1));
+    if (decode_group < 1) decode_group = 1;
+    if (decode_group > n_layers) decode_group = n_layers;
+    // decompress layers [l0, l1) into their working buffers and apply their outlier dictionaries
+    auto decode_layers = [&](int l0, int l1) -> sti_status {
+        const ShardDesc *dev_table = (const ShardDesc *)(ws + wl.table);
+        const size_t lo = first_shard[l0], hi = (l1 < n_layers) ? first_shard[l1] : table.size();
+        if (hi == lo) return STI_OK;
+        STI_TRY(timed(STI_K_DECODE, stream, [&] {
+            return launch_decode_tiled_table(dev_table + lo, (int)(hi - lo), dims->d_model, dims->d_head,
+                                             dims->ffn_per_shard, ws + wl.w16 + lo * wsh * 2, stream);
+        }));
+        for (int l = l0; l < l1; ++l) {   // (absent in most stores)
+            const size_t a = first_shard[l], b = (l + 1 < n_layers) ? first_shard[l + 1] : table.size();
+            uint32_t max_outliers = 0;
+            InlineShardTable t;
+            memset(&t, 0, sizeof(t));
+            for (size_t e = a; e < b; ++e) {
+                t.d[e - a] = table[e];
+                if (table[e].n_outliers > max_outliers) max_outliers = table[e].n_outliers;
+            }
+            if (max_outliers > 0)
+                STI_TRY(launch_patch_outliers_tiled(t, (int)(b - a), max_outliers, dims->d_model, dims->d_head,
+                                                    dims->ffn_per_shard, ws + wl.w16 + a * wsh * 2, stream));
+        }
+        return STI_OK;
+    };
     const sti_dtype act = (precision == STI_PREC_F32) ? STI_F32 : STI_F16;
     const void *cur = x;
     int next_buf = 0;
@@ -643,6 +656,10 @@ sti_status sti_model_forward(const sti_dims *dims, int n_layers, const sti_shard
     for (int l = 0; l < n_layers; ++l) {
         const bool last = (l == n_layers - 1);
         void *out = last ? y : (void *)(ws + wl.act[next_buf]);
+        if (whole_model_fits && !table.empty() && l % decode_group == 0) {
+            st = decode_layers(l, l + decode_group < n_layers ? l + decode_group : n_layers);
+            if (st != STI_OK) return st;
+        }
         const void *predecoded = whole_model_fits ? (const void *)(ws + wl.w16 + first_shard[l] * wsh * 2) : nullptr;
         st = run_layer(*dims, &chosen[(size_t)l * M], params[l], cur, out, last ? io_dtype : act,
                        batch, seq, precision, ws, wl, stream, predecoded);

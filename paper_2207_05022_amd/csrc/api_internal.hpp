@@ -18,8 +18,8 @@ struct WorkspaceLayout {
     size_t w32 = 0, w16 = 0, act[2] = {0, 0}, qkv = 0, ctx = 0, pre = 0, h = 0, u = 0, table = 0, total = 0;
     int w16_layers = 1;   // layers the binary16 working buffer holds at once
 };
-// w16_layers > 1: room for that many layers' binary16 working buffers (decompressed in one
-// launch by sti_model_forward) and for the device copy of their shard table.
+// w16_layers > 1: room for that many layers' binary16 working buffers (decompressed a few
+// layers per launch by sti_model_forward) and for the device copy of their shard table.
 WorkspaceLayout workspace_layout(const sti_dims &d, int64_t T, sti_precision prec, int w16_layers = 1);
 
 sti_status check_dims(const sti_dims *dims, int batch, int seq, sti_precision prec);
