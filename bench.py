@@ -27,10 +27,10 @@ sys.path.insert(0, ROOT)
 TRAFFIC = {
     "gemm": {"files": ("gemm_wide.hip", "weight_loader.hpp", "sti_internal.hpp"),
              "sha256": "cb7469371a557216520a3c34fb31760bbfed51df1731083dfcc34a9ec446927f",
-             "bytes_per_launch": 56811988},
+             "bytes_per_launch": 56811629},
     "decode": {"files": ("decode.hip", "weight_loader.hpp", "sti_internal.hpp"),
                "sha256": "b4097d48d2d6b2c311b2a94bb7e7c449fb68d529cb8ae8006718f0c12a7c7eb7",
-               "bytes_per_launch": 6089427255},
+               "bytes_per_launch": 6089409165},
 }
 
 
