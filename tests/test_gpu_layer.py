@@ -115,6 +115,23 @@ def test_f32_bf16_io(gpu, oracle_mod):
     assert rel_err(y.float().cpu().numpy(), want) <= 8e-3  # output rounded to bfloat16
 
 
+@pytest.mark.parametrize("B,L", [(1, 40), (5, 128)])   # few-token kernels / wide-tile kernels
+def test_mfma_bf16_io(gpu, oracle_mod, B, L):
+    torch, P, D = gpu
+    wl = S.small_workload(11, MID, 2, B, L)
+    xb = torch.from_numpy(wl.x).to(torch.bfloat16)
+    wl.x = xb.float().numpy()
+    want = oracle_mod.model_forward(MID, wl.shards, wl.params, wl.x)
+    shards, params, _ = D.upload_workload(wl)
+    xd = xb.cuda(); y = torch.empty_like(xd)
+    prec = P.STI_PREC_F16_MFMA
+    ws = torch.empty(P.sti_model_workspace_bytes(MID, 2, B, L, prec), dtype=torch.uint8, device="cuda")
+    P.sti_model_forward(MID, D.store_from_plan(shards), params, wl.plan, xd, y, prec, ws)
+    torch.cuda.synchronize()
+    assert y.dtype == torch.bfloat16
+    assert rel_err(y.float().cpu().numpy(), want) <= TOL["mfma"]
+
+
 def test_f32_config0(gpu, oracle_mod):
     wl = S.config0()
     want = oracle_mod.layer_forward(wl.dims, wl.shards[0], wl.params[0], wl.x)
