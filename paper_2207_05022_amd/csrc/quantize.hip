@@ -188,69 +188,100 @@ __device__ inline uint64_t block_scan_1024(uint64_t v, uint64_t *lds, uint64_t *
 }
 
 // single workgroup: outlier list offsets per shard, number of inliers, and for every cluster
-// boundary the high-half bin that holds its rank
+// boundary the high-half bin that holds its rank.  Laid out so that nothing waits on a chain
+// of dependent global loads: one wave scans one shard's chunk counts, a thread keeps its 64
+// bins in registers for the search, and the boundary bins reach the last step through LDS.
 __global__ __launch_bounds__(1024) void select_bins_kernel(QuantState *st, const uint32_t *hist_hi, uint8_t *bin_slot,
                                                            const uint32_t *chunk_count, uint32_t *chunk_off,
                                                            int n_shards, int chunks_per_shard, int n_clusters,
                                                            uint32_t *outlier_count)
 {
     __shared__ uint64_t lds[16];
-    __shared__ uint64_t n_out_total;
-    if (threadIdx.x == 0) n_out_total = 0;
-    __syncthreads();
-    // (a) outlier list offsets: exclusive scan of the chunk counts of each shard
-    for (int s = 0; s < n_shards; ++s) {
-        uint64_t carry = 0;
-        for (int base = 0; base < chunks_per_shard; base += 1024) {
-            const int c = base + threadIdx.x;
-            const uint64_t v = c < chunks_per_shard ? chunk_count[(size_t)s * chunks_per_shard + c] : 0;
-            uint64_t total;
-            const uint64_t pre = block_scan_1024(v, lds, &total);
-            if (c < chunks_per_shard) chunk_off[(size_t)s * chunks_per_shard + c] = (uint32_t)(carry + pre);
-            carry += total;
-            __syncthreads();
+    __shared__ uint32_t shard_outliers[kMaxShardsPerLayer];
+    __shared__ uint32_t l_edge_bin[kMaxClusters];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    // (a) outlier list offsets: exclusive scan of the chunk counts of each shard, 4 chunks per
+    //     lane and step
+    for (int s = wave; s < n_shards; s += 16) {
+        const uint32_t *cnt = chunk_count + (size_t)s * chunks_per_shard;
+        uint32_t *off = chunk_off + (size_t)s * chunks_per_shard;
+        uint32_t carry = 0;
+        for (int base = 0; base < chunks_per_shard; base += 256) {
+            const int c0 = base + lane * 4;
+            uint32_t v[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) v[j] = (c0 + j < chunks_per_shard) ? cnt[c0 + j] : 0;
+            const uint32_t mine = v[0] + v[1] + v[2] + v[3];
+            uint32_t inc = mine;
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) {
+                const uint32_t up = __shfl_up(inc, o, 64);
+                if (lane >= o) inc += up;
+            }
+            uint32_t p = carry + inc - mine;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if (c0 + j < chunks_per_shard) off[c0 + j] = p;
+                p += v[j];
+            }
+            carry += __shfl(inc, 63, 64);
         }
-        if (threadIdx.x == 0) {
-            outlier_count[s] = (uint32_t)carry;
-            n_out_total += carry;
+        if (lane == 0) {
+            outlier_count[s] = carry;
+            shard_outliers[s] = carry;
         }
-        __syncthreads();
     }
+    __syncthreads();
+    uint64_t n_out_total = 0;
+    for (int s = 0; s < n_shards; ++s) n_out_total += shard_outliers[s];
     const uint64_t n_in = st->n_total - n_out_total;
     if (threadIdx.x == 0) {
         st->n_inliers = n_in;
         if (n_in == 0) st->error = 1;
     }
     if (n_in == 0) return;
-    // (b) prefix of the 65536 bins, 64 consecutive bins per thread
+    // (b) prefix of the 65536 bins, 64 consecutive bins per thread (kept in registers)
+    uint32_t h[64];
+    const uint4 *h4 = (const uint4 *)(hist_hi + threadIdx.x * 64);
+#pragma unroll
+    for (int q = 0; q < 16; ++q) {
+        const uint4 x = h4[q];
+        h[4 * q] = x.x; h[4 * q + 1] = x.y; h[4 * q + 2] = x.z; h[4 * q + 3] = x.w;
+    }
     uint64_t own = 0;
-    for (int b = 0; b < 64; ++b) own += hist_hi[threadIdx.x * 64 + b];
+#pragma unroll
+    for (int b = 0; b < 64; ++b) own += h[b];
     uint64_t total;
-    uint64_t pre = block_scan_1024(own, lds, &total);
+    const uint64_t pre = block_scan_1024(own, lds, &total);
     for (int c = 1; c < n_clusters; ++c) {
         const uint64_t rank = ((uint64_t)c * n_in) / (uint64_t)n_clusters;
         if (rank >= pre && rank < pre + own) {
-            uint64_t p = pre;
+            const uint32_t rel = (uint32_t)(rank - pre);   // rank inside this thread's 64 bins
+            uint32_t p = 0;
+            int bin = -1;
+            uint32_t rank_in_bin = 0;
+#pragma unroll
             for (int b = 0; b < 64; ++b) {
-                const uint64_t h = hist_hi[threadIdx.x * 64 + b];
-                if (rank < p + h) {
-                    st->edge_bin[c - 1] = threadIdx.x * 64 + b;
-                    st->edge_rank[c - 1] = (uint32_t)(rank - p);
-                    break;
+                if (bin < 0 && rel < p + h[b]) {
+                    bin = b;
+                    rank_in_bin = rel - p;
                 }
-                p += h;
+                p += h[b];
             }
+            st->edge_bin[c - 1] = threadIdx.x * 64 + bin;
+            st->edge_rank[c - 1] = rank_in_bin;
+            l_edge_bin[c - 1] = threadIdx.x * 64 + bin;
         }
     }
     __syncthreads();
     if (threadIdx.x == 0) {
-        __threadfence();
-        uint32_t n_slots = 0;
+        uint32_t n_slots = 0, last_bin = 0;
         for (int c = 1; c < n_clusters; ++c) {
-            const uint32_t bin = st->edge_bin[c - 1];
-            if (n_slots == 0 || st->slot_bin[n_slots - 1] != bin) {   // boundary bins are non-decreasing
+            const uint32_t bin = l_edge_bin[c - 1];
+            if (n_slots == 0 || last_bin != bin) {   // boundary bins are non-decreasing
                 st->slot_bin[n_slots] = bin;
                 bin_slot[bin] = (uint8_t)(n_slots + 1);
+                last_bin = bin;
                 ++n_slots;
             }
         }
@@ -312,7 +343,7 @@ __device__ inline int cluster_of(uint32_t key, const uint32_t *edges, int n_edge
     return lo;
 }
 
-// per chunk: float64 sum and count of the inliers of every cluster, in a fixed order
+// per chunk: float64 sum and count of the inliers of every cluster
 __global__ __launch_bounds__(256) void cluster_sums_kernel(const float *w, const QuantState *st, int n_clusters,
                                                            double *csum, uint32_t *ccount)
 {
@@ -320,6 +351,8 @@ __global__ __launch_bounds__(256) void cluster_sums_kernel(const float *w, const
     __shared__ double wsum[4][kMaxClusters];
     __shared__ uint32_t wcnt[4][kMaxClusters];
     if (threadIdx.x < n_clusters - 1) edges[threadIdx.x] = st->edge_key[threadIdx.x];
+    (&wsum[0][0])[threadIdx.x] = 0.0;   // 4 x kMaxClusters = 256 accumulators, one per thread
+    (&wcnt[0][0])[threadIdx.x] = 0;
     __syncthreads();
     const double mu = st->mu, r2 = st->r2;
     const f32x4 v = *(const f32x4 *)(w + (size_t)blockIdx.x * kChunk + threadIdx.x * 4);
@@ -329,16 +362,18 @@ __global__ __launch_bounds__(256) void cluster_sums_kernel(const float *w, const
         const double d = (double)v[e] - mu;
         idx[e] = (d * d > r2) ? -1 : cluster_of(order_key(v[e]), edges, n_clusters - 1);
     }
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    for (int c = 0; c < n_clusters; ++c) {
-        double s = 0.0;
-        uint32_t n = 0;
+    const int wave = threadIdx.x >> 6;
+    // every wave adds into accumulators of its own with LDS atomics (float64 add, integer add):
+    // four instructions per kind and wave instead of a shuffle reduction per cluster.  Lanes
+    // of one instruction that hit the same cluster are added in the order the LDS serialises
+    // them; float64 sums of at most 256 float32 values agree to ~1e-16 relative in any order,
+    // and the centroid is rounded to float32 once, from the sum over all chunks.
 #pragma unroll
-        for (int e = 0; e < 4; ++e)
-            if (idx[e] == c) { s += (double)(v[e] + 0.0f); n += 1; }
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) { s += __shfl_down(s, o, 64); n += __shfl_down(n, o, 64); }
-        if (lane == 0) { wsum[wave][c] = s; wcnt[wave][c] = n; }
+    for (int e = 0; e < 4; ++e) {
+        if (idx[e] >= 0) {
+            unsafeAtomicAdd(&wsum[wave][idx[e]], (double)(v[e] + 0.0f));
+            atomicAdd(&wcnt[wave][idx[e]], 1u);
+        }
     }
     __syncthreads();
     if (threadIdx.x < n_clusters) {

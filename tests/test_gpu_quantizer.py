@@ -68,6 +68,20 @@ def test_quantizer_matches_reference(k):
     check_against_reference(MID, w, k, g)
 
 
+def test_quantizer_repeats_bit_for_bit():
+    """The same input gives the same codebook, streams and dictionaries on every call, at the
+    BERT-base shard size (576 chunks per shard, 6-bit: 64 clusters per LDS accumulator set)."""
+    dims = S.Dims(768, 2, 64, 256, 1e-12)
+    w = layer_weights(77, dims)
+    a = run_gpu(dims, w, 6, max_out=4096)
+    for _ in range(3):
+        b = run_gpu(dims, w, 6, max_out=4096)
+        assert np.array_equal(a["codebook"].cpu().numpy().view(np.uint32), b["codebook"].cpu().numpy().view(np.uint32))
+        assert bool((a["packed"] == b["packed"]).all())
+        assert bool((a["cnt"] == b["cnt"]).all())
+    check_against_reference(dims, w, 6, a)
+
+
 def test_quantize_then_decode_round_trip():
     """Quantizer output -> sti_decode_shards (substitution + outliers written back) equals the
     reference's dequantized weights bit for bit."""
