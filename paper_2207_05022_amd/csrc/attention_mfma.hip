@@ -8,8 +8,9 @@
 //   O^T = V^T P^T -> the probabilities are already in the register layout the
 //                    B operand needs once the key order inside each k16 step
 //                    is permuted, and V^T is read from LDS in that same order.
-// The running max / sum (online softmax) is per lane; lanes l and l^32 own the
-// two halves of a query's keys and exchange their maxima once per key block.
+// The maximum and the sum of a query's row are per lane; lanes l and l^32 own the two
+// halves of a query's keys and exchange their maxima (once per key block with the running
+// maximum of the online softmax, once in all when the sequence is short, see SHORT).
 #include "sti_internal.hpp"
 
 namespace sti {
