@@ -191,8 +191,9 @@ sti_status sti_model_forward(const sti_dims *dims, int n_layers, const sti_shard
 /* Workspace size with which sti_model_forward decompresses several layers per launch
  * (Section "Submodel execution" keeps one layer's working buffer because memory is scarce on
  * the paper's devices; with room for one buffer per layer, a few layers are decompressed by
- * one launch right before the first of them runs).  Applies to STI_PREC_F16_MFMA from 512
- * tokens on; otherwise, and for n_layers <= 1, it equals sti_workspace_bytes.
+ * one launch right before the first of them runs).  Applies to STI_PREC_F16_MFMA whenever
+ * the layer goes through the working buffer (more than 128 tokens, more than 192 when
+ * d_model <= 768); otherwise, and for n_layers <= 1, it equals sti_workspace_bytes.
  * sti_model_forward takes the grouped route whenever workspace_bytes is at least this value
  * and the per-layer route otherwise: same results either way.  0 on invalid arguments. */
 size_t sti_model_workspace_bytes(const sti_dims *dims, int n_layers, int batch, int seq,

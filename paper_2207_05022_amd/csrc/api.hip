@@ -252,7 +252,18 @@ inline const void *block_start(const sti_shard &s, size_t elem_off)
 // From this many tokens on, a layer's shards are decompressed once into the binary16
 // working buffer; below it, the GEMMs decode the streams themselves (every weight is then
 // used by at most a few row tiles).
-constexpr int kWorkingBufferMinTokens = 512;
+// Which GEMM family a matrix-core layer takes.  The few-token kernels decode every weight
+// once per 64-row block and take partial sums through LayerNorm; from a couple of row blocks
+// on it is cheaper to decompress the layer once into the working buffer and run the
+// wide-tile kernels (measured per layer, BERT-base with 9 of 12 shards: 128 tokens 57 against
+// 69 us, 192 tokens 60 against 63, 256 tokens 68 against 65, 384 tokens 164 -- with the
+// decode fused into a tiled GEMM, as used before -- against 70; d_model 1024, 12 of 16 shards:
+// 192 tokens 82 against 76, 256 tokens 92 against 77).
+inline bool few_token_path(const sti_dims &d, int64_t T)
+{
+    return T <= 128 || (T <= 192 && d.d_model <= 768);
+}
+static_assert(kSkinnyMaxTokens >= 192, "the partial-sum planes are sized with kSkinnyMaxTokens");
 
 
 // One layer, arguments already validated.  `in` is float32 (F32 precision) or
@@ -284,8 +295,7 @@ sti_status run_layer(const sti_dims &d, const sti_shard *shards, const sti_layer
         if (shards[present[p]].n_outliers > max_outliers) max_outliers = shards[present[p]].n_outliers;
     // shards with an outlier dictionary always go through the working buffer, where the
     // outliers are scattered back after the substitution pass
-    const bool predecode = !f32 && m > 0 && (predecoded || T >= kWorkingBufferMinTokens || max_outliers > 0);
-    static_assert(kWorkingBufferMinTokens > kSkinnyMaxTokens, "the few-token GEMM decodes in registers");
+    const bool predecode = !f32 && m > 0 && (predecoded || !few_token_path(d, T) || max_outliers > 0);
     const _Float16 *w16 = predecoded ? (const _Float16 *)predecoded : (const _Float16 *)(ws + wl.w16);
     if (predecode && !predecoded) {
         InlineShardTable t;
@@ -331,7 +341,7 @@ sti_status run_layer(const sti_dims &d, const sti_shard *shards, const sti_layer
     void *qkv = ws + wl.qkv, *ctx = ws + wl.ctx, *h = ws + wl.h, *u = ws + wl.u;
     float *pre = (float *)(ws + wl.pre);
     const sti_dtype act_dtype = f32 ? STI_F32 : STI_F16;
-    const bool skinny = !f32 && T <= kSkinnyMaxTokens;
+    const bool skinny = !f32 && few_token_path(d, T);
     const int64_t partial_stride = (int64_t)T * dm;
     int pre_partials = 1;   // partial sums the last K-split GEMM left in `pre`
     auto gemm = [&](const GemmProblem &p, const GemmBlocks &blk) {
@@ -578,7 +588,7 @@ sti_status sti_model_forward(const sti_dims *dims, int n_layers, const sti_shard
     // one buffer just before it runs.
     WorkspaceLayout wl = workspace_layout(*dims, T, precision);
     const bool whole_model_fits =
-        precision == STI_PREC_F16_MFMA && T >= kWorkingBufferMinTokens && n_layers > 1 &&
+        precision == STI_PREC_F16_MFMA && !few_token_path(*dims, T) && n_layers > 1 &&
         workspace_bytes >= workspace_layout(*dims, T, precision, n_layers).total;
     if (whole_model_fits) wl = workspace_layout(*dims, T, precision, n_layers);
     if (!workspace || workspace_bytes < wl.total) return STI_ERR_WORKSPACE;
@@ -674,7 +684,7 @@ size_t sti_model_workspace_bytes(const sti_dims *dims, int n_layers, int batch, 
 {
     if (check_dims(dims, batch, seq, precision) != STI_OK || n_layers < 0) return 0;
     const int64_t T = (int64_t)batch * seq;
-    const bool whole_model = precision == STI_PREC_F16_MFMA && T >= kWorkingBufferMinTokens && n_layers > 1;
+    const bool whole_model = precision == STI_PREC_F16_MFMA && !few_token_path(*dims, T) && n_layers > 1;
     return workspace_layout(*dims, T, precision, whole_model ? n_layers : 1).total;
 }
 

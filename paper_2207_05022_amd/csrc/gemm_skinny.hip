@@ -1,4 +1,4 @@
-// Projections for few tokens (T <= 256): the regime of single-sequence inference, where
+// Projections for few tokens (up to 128-192, at most 256): the regime of single-sequence inference, where
 // every weight is used once and the layer is bound by how fast the packed shards stream in
 // (Section "Submodel execution" runs one input at a time).
 //

@@ -106,7 +106,7 @@ bool gemm_wide_supported(const GemmProblem &p, const GemmBlocks &blocks);
 hipError_t launch_attention_mfma(const void *qkv, void *ctx, int B, int L, int m, int dh,
                                  hipStream_t stream);
 
-// Few-token variant of the MFMA GEMM (gemm_skinny.hip): T <= 256, split-K inside the
+// Few-token variant of the MFMA GEMM (gemm_skinny.hip): T <= kSkinnyMaxTokens, split-K inside the
 // workgroup and, for the K-split kinds, across `k_splits` workgroups that write float32
 // partial sums at C + s * partial_stride (to be added by launch_layernorm).
 constexpr int kSkinnyMaxTokens = 256;

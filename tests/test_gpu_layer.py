@@ -284,7 +284,7 @@ def test_mfma_whole_model_decode_matches_per_layer_route(gpu, oracle_mod):
     assert torch.equal(outs[0], outs[1])
     want = oracle_mod.model_forward(wl.dims, wl.shards, wl.params, wl.x)
     assert rel_err(outs[1].float().cpu().numpy(), want) <= TOL["mfma"]
-    # below 512 tokens the query falls back to the one-layer size
+    # on the few-token route the query falls back to the one-layer size
     assert P.sti_model_workspace_bytes(wl.dims, wl.n_layers, 1, 128, prec) == P.sti_workspace_bytes(wl.dims, 1, 128, prec)
 
 
