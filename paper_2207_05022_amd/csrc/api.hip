@@ -194,6 +194,10 @@ WorkspaceLayout workspace_layout(const sti_dims &d, int64_t T, sti_precision pre
     {   // float32 sums before LayerNorm; the few-token GEMM may leave several partial sums
         size_t rows = (size_t)T;
         if (prec != STI_PREC_F32 && T <= kSkinnyMaxTokens) rows *= kSkinnyMaxSplits;
+        if (prec != STI_PREC_F32) {   // ... and so may the wide-tile GEMM when it has few tiles
+            const size_t wide_rows = (size_t)T * gemm_wide_max_k_splits(T, (int)dm);
+            if (wide_rows > rows) rows = wide_rows;
+        }
         L.pre = take(rows * dm * 4);
     }
     L.h = take((size_t)T * dm * es);
@@ -349,7 +353,15 @@ sti_status run_layer(const sti_dims &d, const sti_shard *shards, const sti_layer
                                    STI_K_GEMM_FFN_DOWN};
         return timed(cls[p.kind], stream, [&] {
             if (f32) return launch_gemm_f32(p, blk, stream);
-            if (!skinny) return launch_gemm_mfma(p, blk, stream);
+            if (!skinny) {
+                GemmProblem q = p;
+                if ((p.kind == GEMM_OUT || p.kind == GEMM_FFN_DOWN) && gemm_wide_supported(p, blk)) {
+                    q.k_splits = gemm_wide_k_splits(p);
+                    q.partial_stride = partial_stride;
+                    pre_partials = q.k_splits;
+                }
+                return launch_gemm_mfma(q, blk, stream);
+            }
             const int splits = skinny_k_splits(p);
             if (p.kind == GEMM_OUT || p.kind == GEMM_FFN_DOWN) pre_partials = splits;
             return launch_gemm_skinny(p, blk, splits, partial_stride, stream);
@@ -359,7 +371,7 @@ sti_status run_layer(const sti_dims &d, const sti_shard *shards, const sti_layer
     auto layernorm = [&](void *dst, sti_dtype dt, const float *g, const float *b,
                          const float *bias, const void *resid) {
         return timed(STI_K_LAYERNORM, stream, [&] {
-            if (!f32 && !skinny)   // the wide MFMA GEMM already added bias and residual
+            if (!f32 && !skinny && pre_partials == 1)   // the wide MFMA GEMM already added bias and residual
                 return launch_layernorm_f16in(pre, dst, dt, g, b, T, dm, d.ln_eps, stream);
             return launch_layernorm(pre, pre_partials, partial_stride, f32 ? nullptr : bias,
                                     f32 ? nullptr : resid, dst, dt, g, b, T, dm, d.ln_eps, stream);

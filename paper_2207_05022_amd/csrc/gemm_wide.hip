@@ -82,11 +82,14 @@ __global__ __launch_bounds__(NW * KS * 64, 3) void gemm_wide_kernel(GemmProblem 
 
     const int N = n_split ? p.n_blocks * p.block_rows : p.block_rows;
     const int K = n_split ? p.block_cols : p.n_blocks * p.block_cols;
-    const int nkt = K / BK / KS;           // K tiles of this wave's group
+    // K is split over the KS wave groups of the workgroup and, for few tiles, over
+    // gridDim.y workgroups per tile as well (raw float32 partial sums, see the epilogue)
+    const int splits = (!n_split && p.k_splits > 1) ? p.k_splits : 1;
+    const int nkt = K / BK / KS / splits;  // K tiles of this wave's group
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave_all = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int half = wave_all / NW, wave = wave_all - half * NW;   // K group, column strip
-    const int kt0 = half * nkt;
+    const int kt0 = ((int)blockIdx.y * KS + half) * nkt;
     const int g = lane >> 5, lr = lane & 31;
     // Workgroups are handed to the 8 XCDs round-robin by linear id; give each XCD one
     // contiguous range of the row-major tile order.
@@ -276,6 +279,35 @@ __global__ __launch_bounds__(NW * KS * 64, 3) void gemm_wide_kernel(GemmProblem 
         }
         __syncthreads();   // the sums are in registers: the buffer can take the staged tile
     }
+    if (splits > 1) {
+        // one of several workgroups of this tile: raw float32 sums, 32 bytes per lane and piece
+        if (half == 0 && nw_real < N) {
+            float *Cf = (float *)p.C + (int64_t)blockIdx.y * p.partial_stride;
+#pragma unroll
+            for (int i = 0; i < RA; ++i) {
+                const int m = m0 + i * 32 + lr;
+#pragma unroll
+                for (int q = 0; q < 2; ++q) {
+                    float x[8];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float lo = acc[i][(2 * q) * 4 + e], hi = acc[i][(2 * q + 1) * 4 + e];
+                        const auto sw = __builtin_amdgcn_permlane32_swap(__builtin_bit_cast(uint32_t, lo),
+                                                                         __builtin_bit_cast(uint32_t, hi), false, false);
+                        const uint32_t s0 = sw[0], s1 = sw[1];
+                        x[e] = __builtin_bit_cast(float, s0);
+                        x[4 + e] = __builtin_bit_cast(float, s1);
+                    }
+                    if (m < p.T) {
+                        float *dst = Cf + (int64_t)m * p.ldc + nw + 16 * q + 8 * g;
+                        *(f32x4 *)dst = f32x4{x[0], x[1], x[2], x[3]};
+                        *(f32x4 *)(dst + 4) = f32x4{x[4], x[5], x[6], x[7]};
+                    }
+                }
+            }
+        }
+        return;
+    }
     if (half == 0) {
 #pragma unroll
     for (int i = 0; i < RA; ++i) {
@@ -348,7 +380,8 @@ hipError_t launch_shape(const GemmProblem &p, const GemmBlocks &blocks, int N, h
         attr_set = true;
     }
     const int total = ((N + BN - 1) / BN) * ((p.T + BM - 1) / BM);
-    dim3 grid(((total + 7) / 8) * 8);
+    const bool n_split = (KIND == GEMM_QKV || KIND == GEMM_FFN_UP);
+    dim3 grid(((total + 7) / 8) * 8, (!n_split && p.k_splits > 1) ? p.k_splits : 1);
     gemm_wide_kernel<KIND, RA, NW, KS><<<grid, dim3(NW * KS * 64), lds, stream>>>(p, blocks);
     return hipGetLastError();
 }
@@ -388,15 +421,20 @@ bool gemm_wide_supported(const GemmProblem &p, const GemmBlocks &blocks)
     return true;
 }
 
-hipError_t launch_gemm_wide(const GemmProblem &p, const GemmBlocks &blocks, hipStream_t stream)
+namespace {
+
+struct Choice {
+    int shape;       // index into kShapes
+    bool ks2;        // K split over two wave groups inside the workgroup
+    long tiles;
+    int nkt_total;
+};
+
+Choice choose(const GemmProblem &p, int N)
 {
     const bool n_split = (p.kind == GEMM_QKV || p.kind == GEMM_FFN_UP);
-    const int N = n_split ? p.n_blocks * p.block_rows : p.block_rows;
-    if (p.T <= 0 || N <= 0) return hipSuccess;
-    if (!gemm_wide_supported(p, blocks)) return hipErrorInvalidValue;
-    if (N % 32 || p.block_rows % 32 || p.block_cols % BK || p.lda % 8 || p.ldc % 8) return hipErrorInvalidValue;
     int best = -1;
-    long best_key[4] = {0, 0, 0, 0};
+    long best_key[4] = {0, 0, 0, 0}, best_tiles = 0;
     for (int c = 0; c < (int)(sizeof(kShapes) / sizeof(kShapes[0])); ++c) {
         const int bm = kShapes[c].ra * 32, bn = kShapes[c].nw * 32;
         const long tiles = (long)((N + bn - 1) / bn) * ((p.T + bm - 1) / bm);
@@ -412,17 +450,60 @@ hipError_t launch_gemm_wide(const GemmProblem &p, const GemmBlocks &blocks, hipS
         }
         if (better) {
             best = c;
+            best_tiles = tiles;
             for (int i = 0; i < 4; ++i) best_key[i] = key[i];
         }
     }
-    const int nkt_total = (n_split ? p.block_cols : p.n_blocks * p.block_cols) / BK;
-    if (!n_split && kShapes[best].ra == 2 && kShapes[best].nw == 6 && best_key[1] == 1 &&
-        best_key[0] == 12 && nkt_total % 2 == 0 && nkt_total >= 4) {
-        // one 6-wave workgroup per unit: split K inside the workgroup to fill the unit
+    Choice ch;
+    ch.shape = best;
+    ch.tiles = best_tiles;
+    ch.nkt_total = (n_split ? p.block_cols : p.n_blocks * p.block_cols) / BK;
+    // one 6-wave workgroup per unit: split K inside the workgroup to fill the unit
+    ch.ks2 = !n_split && kShapes[best].ra == 2 && kShapes[best].nw == 6 && best_key[1] == 1 &&
+             best_key[0] == 12 && ch.nkt_total % 2 == 0 && ch.nkt_total >= 4;
+    return ch;
+}
+
+}  // namespace
+
+// With few tiles (few tokens) a workgroup of the d_model-wide projections would walk a long K
+// range alone while most compute units idle (FFN2 at 256 tokens: 16 workgroups, 21 us): K is
+// then split over 2 or 4 workgroups per tile as well, each with at least 3 K tiles per wave
+// group, while they fill at most half the chip (measured: 3-6 % per layer from 256 to 1024
+// tokens; 8 splits, or splitting up to the whole chip, cost more in the LayerNorm that adds
+// the float32 partial sums than they save here).
+int gemm_wide_k_splits(const GemmProblem &p)
+{
+    if (p.kind == GEMM_QKV || p.kind == GEMM_FFN_UP || p.n_blocks <= 0 || p.T <= 0) return 1;
+    const Choice ch = choose(p, p.block_rows);
+    if (!ch.ks2) return 1;
+    for (int s = 4; s >= 2; s >>= 1)
+        if (ch.tiles * s <= kComputeUnits / 2 && ch.nkt_total % (2 * s) == 0 && ch.nkt_total / (2 * s) >= 3) return s;
+    return 1;
+}
+
+int gemm_wide_max_k_splits(int64_t T, int N)
+{
+    const int64_t tiles = ((T + 63) / 64) * ((N + 191) / 192);
+    for (int s = 4; s >= 2; s >>= 1)
+        if (tiles * s <= kComputeUnits / 2) return s;
+    return 1;
+}
+
+hipError_t launch_gemm_wide(const GemmProblem &p, const GemmBlocks &blocks, hipStream_t stream)
+{
+    const bool n_split = (p.kind == GEMM_QKV || p.kind == GEMM_FFN_UP);
+    const int N = n_split ? p.n_blocks * p.block_rows : p.block_rows;
+    if (p.T <= 0 || N <= 0) return hipSuccess;
+    if (!gemm_wide_supported(p, blocks)) return hipErrorInvalidValue;
+    if (N % 32 || p.block_rows % 32 || p.block_cols % BK || p.lda % 8 || p.ldc % 8) return hipErrorInvalidValue;
+    const Choice ch = choose(p, N);
+    if (p.k_splits > 1 && (!ch.ks2 || p.k_splits != gemm_wide_k_splits(p))) return hipErrorInvalidValue;
+    if (ch.ks2) {
         return p.kind == GEMM_OUT ? launch_shape<GEMM_OUT, 2, 6, 2>(p, blocks, N, stream)
                                   : launch_shape<GEMM_FFN_DOWN, 2, 6, 2>(p, blocks, N, stream);
     }
-    switch (best) {
+    switch (ch.shape) {
     case 0: return launch_kind<4, 12>(p, blocks, N, stream);
     case 1: return launch_kind<4, 9>(p, blocks, N, stream);
     case 2: return launch_kind<2, 12>(p, blocks, N, stream);

@@ -85,6 +85,11 @@ struct GemmProblem {
     const float *bias0, *bias1, *bias2;  // QKV: bq,bk,bv; FFN_UP: b1; OUT/FFN_DOWN: bias[N]
     const void *resid;  // OUT/FFN_DOWN: [T x N] residual, row stride ldr
     int32_t ldr;
+    // wide-tile kernel, OUT/FFN_DOWN only: with k_splits > 1 the K range is also split over
+    // that many workgroups per tile, C is float32 and takes the raw partial sums of split s
+    // at C + s * partial_stride (bias and residual are left to launch_layernorm)
+    int32_t k_splits;
+    int64_t partial_stride;
 };
 
 // float32 path (layer_f32.hip): A, C, resid are float32; weights are float32 blocks.
@@ -103,6 +108,10 @@ hipError_t launch_gemm_mfma(const GemmProblem &p, const GemmBlocks &blocks, hipS
 // binary16 working buffer (bits == kTiledBits); launch_gemm_mfma forwards such problems here.
 hipError_t launch_gemm_wide(const GemmProblem &p, const GemmBlocks &blocks, hipStream_t stream);
 bool gemm_wide_supported(const GemmProblem &p, const GemmBlocks &blocks);
+// K splits across workgroups the wide-tile kernel wants for this problem (1 = none), and the
+// largest value it can return for T tokens and N output columns (workspace sizing)
+int gemm_wide_k_splits(const GemmProblem &p);
+int gemm_wide_max_k_splits(int64_t T, int N);
 hipError_t launch_attention_mfma(const void *qkv, void *ctx, int B, int L, int m, int dh,
                                  hipStream_t stream);
 
