@@ -355,12 +355,12 @@ sti_status run_layer(const sti_dims &d, const sti_shard *shards, const sti_layer
             if (f32) return launch_gemm_f32(p, blk, stream);
             if (!skinny) {
                 GemmProblem q = p;
-                if ((p.kind == GEMM_OUT || p.kind == GEMM_FFN_DOWN) && gemm_wide_supported(p, blk)) {
+                if (p.kind == GEMM_OUT || p.kind == GEMM_FFN_DOWN) {
                     q.k_splits = gemm_wide_k_splits(p);
                     q.partial_stride = partial_stride;
                     pre_partials = q.k_splits;
                 }
-                return launch_gemm_mfma(q, blk, stream);
+                return launch_gemm_wide(q, blk, stream);
             }
             const int splits = skinny_k_splits(p);
             if (p.kind == GEMM_OUT || p.kind == GEMM_FFN_DOWN) pre_partials = splits;

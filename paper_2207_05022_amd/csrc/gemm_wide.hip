@@ -123,14 +123,13 @@ __global__ __launch_bounds__(NW * KS * 64, 3) void gemm_wide_kernel(GemmProblem 
     //      rows with the chunk (l%8) ^ ((row/2)%8) of that row, so that the 16 rows that one
     //      quarter of a fragment read touches (128-byte rows, two per 64-bank line) fall on
     //      16 different bank groups; rows past T repeat row T-1 ----
-    const _Float16 *A = (const _Float16 *)p.A;
-    uint32_t src[FPW];   // byte offset of this lane's chunk from the start of its K tile
+    const _Float16 *A = (const _Float16 *)p.A + (int64_t)m0 * p.lda;   // first row of the tile
+    uint32_t src[FPW];   // byte offset of this lane's chunk from the tile's first row and K tile
 #pragma unroll
     for (int j = 0; j < FPW; ++j) {
-        int m = m0 + (wave + NW * j) * 8 + (lane >> 3);
-        m = m < p.T ? m : p.T - 1;
         const int row = (wave + NW * j) * 8 + (lane >> 3);   // row inside the tile
-        src[j] = (uint32_t)(((int64_t)m * p.lda + (((lane & 7) ^ ((row >> 1) & 7)) * 8)) * 2);
+        const int r = m0 + row < p.T ? row : p.T - 1 - m0;
+        src[j] = (uint32_t)((r * p.lda + (((lane & 7) ^ ((row >> 1) & 7)) * 8)) * 2);   // < 2^24 * 2
     }
     // The loads of the K loop are written as instructions rather than through the compiler:
     // its own bookkeeping would wait for every outstanding fetch into LDS before the next LDS
@@ -416,8 +415,6 @@ bool gemm_wide_supported(const GemmProblem &p, const GemmBlocks &blocks)
     if (p.n_blocks <= 0 || p.T <= 0) return false;
     for (int b = 0; b < p.n_blocks; ++b)
         if (blocks.b[b].bits != kTiledBits) return false;
-    // the A fetches address rows with 32-bit byte offsets from a scalar base
-    if ((int64_t)p.T * p.lda * 2 >= ((int64_t)1 << 31)) return false;
     return true;
 }
 

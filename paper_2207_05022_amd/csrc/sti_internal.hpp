@@ -98,14 +98,11 @@ hipError_t launch_gemm_f32(const GemmProblem &p, const GemmBlocks &blocks, hipSt
 hipError_t launch_attention_f32(const float *qkv, float *ctx, int B, int L, int m, int dh,
                                 hipStream_t stream);
 
-// binary16 MFMA path (gemm_mfma.hip, attention_mfma.hip): A and C are binary16.  QKV / FFN_UP
+// binary16 MFMA path (gemm_wide.hip, attention_mfma.hip): A and C are binary16.  QKV / FFN_UP
 // apply bias (and GELU); OUT / FFN_DOWN add bias[N] and the binary16 residual, leaving the
-// LayerNorm to launch_layernorm_f16in.  Weights are decoded inside the loader or come from
-// the fragment-tiled working buffer.  (The few-token variant below leaves float32 partial
-// sums instead, which launch_layernorm completes.)
-hipError_t launch_gemm_mfma(const GemmProblem &p, const GemmBlocks &blocks, hipStream_t stream);
-// gemm_wide.hip: the same projections when every block is a cell array of the fragment-tiled
-// binary16 working buffer (bits == kTiledBits); launch_gemm_mfma forwards such problems here.
+// LayerNorm to launch_layernorm_f16in (or, with k_splits > 1, leave float32 partial sums that
+// launch_layernorm completes, like the few-token variant below).  Every block is a cell array
+// of the fragment-tiled binary16 working buffer (bits == kTiledBits).
 hipError_t launch_gemm_wide(const GemmProblem &p, const GemmBlocks &blocks, hipStream_t stream);
 bool gemm_wide_supported(const GemmProblem &p, const GemmBlocks &blocks);
 // K splits across workgroups the wide-tile kernel wants for this problem (1 = none), and the

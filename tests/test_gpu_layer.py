@@ -303,6 +303,32 @@ def test_mfma_working_buffer_gemm_tile_shapes(gpu, oracle_mod, B, L, n_absent):
     assert rel_err(got, want) <= TOL["mfma"]
 
 
+def test_mfma_rows_beyond_2gib_of_activations(gpu):
+    """350,000 tokens: the FFN activations (T x 3072 binary16) pass 2 GiB, so row addresses need
+    64 bits.  Sequences are independent, so the first and the last sequence of the big batch
+    must come out as when they run alone (up to the summation order of other tile shapes)."""
+    torch, P, D = gpu
+    dims = S.BERT_BASE
+    B, L = 700, 500
+    wl = S.small_workload(4242, dims, 1, 2, L, io_dtype="f16")
+    shards, params, x2 = D.upload_workload(wl)
+    prec = P.STI_PREC_F16_MFMA
+    gen = torch.Generator(device="cuda").manual_seed(7)
+    x = torch.randn(B, L, dims.d_model, device="cuda", generator=gen).to(torch.float16)
+    x[0] = x2[0]
+    x[B - 1] = x2[1]
+    y = torch.empty_like(x)
+    ws = torch.empty(P.sti_workspace_bytes(dims, B, L, prec), dtype=torch.uint8, device="cuda")
+    P.sti_layer_forward(dims, shards[0], params[0], x, y, prec, ws)
+    y2 = torch.empty_like(x2)
+    ws2 = torch.empty(P.sti_workspace_bytes(dims, 2, L, prec), dtype=torch.uint8, device="cuda")
+    P.sti_layer_forward(dims, shards[0], params[0], x2, y2, prec, ws2)
+    torch.cuda.synchronize()
+    assert torch.isfinite(y).all()
+    for big, alone in ((y[0], y2[0]), (y[B - 1], y2[1])):
+        assert rel_err(big.float().cpu().numpy(), alone.float().cpu().numpy()) <= 4e-3
+
+
 def test_model_forward_can_be_stream_captured(gpu, oracle_mod):
     """The few-token path enqueues kernels only (no copies, no fills, no host waits), so a
     caller may capture it into a graph; replays, with eager calls between them, must give the
