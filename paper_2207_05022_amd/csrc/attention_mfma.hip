@@ -28,9 +28,9 @@ constexpr int KPAD = DH + 8;   // padded K row (halves)
 __device__ inline int vt_stride(int Lp) { return Lp + 8; }
 
 // NW waves per workgroup, 32 queries each.
-// SHORT (at most 128 keys): all scores stay in registers, the row maximum is known before the
-// first exponential, and the output accumulators are never rescaled.
-template <int NW, bool SHORT>
+// SHORT > 0 (at most 32 * SHORT keys; 4 or 8): all scores stay in registers, the row maximum is
+// known before the first exponential, and the output accumulators are never rescaled.
+template <int NW, int SHORT>
 __global__ __launch_bounds__(NW * 64, 2) void attention_mfma_kernel(const _Float16 *qkv, _Float16 *ctx,
                                                                  int L, int Lp, int m)
 {
@@ -133,11 +133,11 @@ __global__ __launch_bounds__(NW * 64, 2) void attention_mfma_kernel(const _Float
             }
         }
     };
-    if constexpr (SHORT) {
-        float16v sc[4];
+    if constexpr (SHORT > 0) {
+        float16v sc[SHORT];
         float mx = -INFINITY;
 #pragma unroll
-        for (int kb = 0; kb < 4; ++kb) {
+        for (int kb = 0; kb < SHORT; ++kb) {
             if (kb >= nkb) break;
 #pragma unroll
             for (int v = 0; v < 16; ++v) sc[kb][v] = 0.f;
@@ -159,7 +159,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attention_mfma_kernel(const _Float
         mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
         const float shift = -mx * scale;   // (scale > 0: the maximum of the scaled scores)
 #pragma unroll
-        for (int kb = 0; kb < 4; ++kb) {
+        for (int kb = 0; kb < SHORT; ++kb) {
             if (kb >= nkb) break;
             uint32_t pk[8];
 #pragma unroll
@@ -239,10 +239,10 @@ hipError_t launch_attention_mfma(const void *qkv, void *ctx, int B, int L, int m
     const size_t lds = ((size_t)Lp * KPAD + (size_t)DH * (Lp + 8)) * sizeof(_Float16);
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)attention_mfma_kernel<4, false>,
+        hipError_t e = hipFuncSetAttribute((const void *)attention_mfma_kernel<4, 0>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e == hipSuccess)
-            e = hipFuncSetAttribute((const void *)attention_mfma_kernel<2, false>,
+            e = hipFuncSetAttribute((const void *)attention_mfma_kernel<2, 0>,
                                     hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
         attr_set = true;
@@ -252,19 +252,25 @@ hipError_t launch_attention_mfma(const void *qkv, void *ctx, int B, int L, int m
     if (small_wg) {
         dim3 grid((L + 63) / 64, m, B);
         if (Lp <= 128)
-            attention_mfma_kernel<2, true><<<grid, dim3(128), lds, stream>>>((const _Float16 *)qkv,
-                                                                             (_Float16 *)ctx, L, Lp, m);
+            attention_mfma_kernel<2, 4><<<grid, dim3(128), lds, stream>>>((const _Float16 *)qkv,
+                                                                          (_Float16 *)ctx, L, Lp, m);
+        else if (Lp <= 256)
+            attention_mfma_kernel<2, 8><<<grid, dim3(128), lds, stream>>>((const _Float16 *)qkv,
+                                                                          (_Float16 *)ctx, L, Lp, m);
         else
-            attention_mfma_kernel<2, false><<<grid, dim3(128), lds, stream>>>((const _Float16 *)qkv,
-                                                                              (_Float16 *)ctx, L, Lp, m);
+            attention_mfma_kernel<2, 0><<<grid, dim3(128), lds, stream>>>((const _Float16 *)qkv,
+                                                                          (_Float16 *)ctx, L, Lp, m);
     } else {
         dim3 grid((L + 127) / 128, m, B);
         if (Lp <= 128)
-            attention_mfma_kernel<4, true><<<grid, dim3(256), lds, stream>>>((const _Float16 *)qkv,
-                                                                             (_Float16 *)ctx, L, Lp, m);
+            attention_mfma_kernel<4, 4><<<grid, dim3(256), lds, stream>>>((const _Float16 *)qkv,
+                                                                          (_Float16 *)ctx, L, Lp, m);
+        else if (Lp <= 256)
+            attention_mfma_kernel<4, 8><<<grid, dim3(256), lds, stream>>>((const _Float16 *)qkv,
+                                                                          (_Float16 *)ctx, L, Lp, m);
         else
-            attention_mfma_kernel<4, false><<<grid, dim3(256), lds, stream>>>((const _Float16 *)qkv,
-                                                                              (_Float16 *)ctx, L, Lp, m);
+            attention_mfma_kernel<4, 0><<<grid, dim3(256), lds, stream>>>((const _Float16 *)qkv,
+                                                                          (_Float16 *)ctx, L, Lp, m);
     }
     return hipGetLastError();
 }

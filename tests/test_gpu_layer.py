@@ -169,9 +169,10 @@ def test_empty_batch_and_zero_layers(gpu):
 
 # ------------------------------------------------------------------ binary16 matrix-core path
 
-# (96, 97, 127: the last 32-key block of the short-sequence attention path full, one key in, one short)
+# (96, 97, 127, and 224, 225, 255: the last 32-key block of the two short-sequence attention paths
+# full, one key in, one short; 256, 257: the longest short sequence and the first long one)
 @pytest.mark.parametrize("B,L", [(1, 1), (2, 33), (1, 128), (3, 100), (1, 300), (2, 96), (2, 97), (1, 127),
-                                 (1, 129), (40, 128)])
+                                 (1, 129), (40, 128), (1, 224), (2, 225), (1, 255), (3, 256), (1, 257)])
 def test_mfma_small_mixed_layer(gpu, oracle_mod, B, L):
     wl = S.small_workload(200 + L, MID, 1, B, L, plan=np.array([[3, 32, 6, 5]]))
     want = oracle_mod.layer_forward(MID, wl.shards[0], wl.params[0], wl.x)
