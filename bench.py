@@ -27,10 +27,10 @@ sys.path.insert(0, ROOT)
 TRAFFIC = {
     "gemm": {"files": ("gemm_wide.hip", "weight_loader.hpp", "sti_internal.hpp"),
              "sha256": "ca7f9258adc6611895662f43a01538d168c5f589932b50bb09e9c38c051b9c6f",
-             "bytes_per_launch": 56818054},
+             "bytes_per_launch": 56818056},
     "decode": {"files": ("decode.hip", "weight_loader.hpp", "sti_internal.hpp"),
                "sha256": "721f89acbbb373b422dbd50b3317c0b195d8ea3fdd2940394d53df5b5d72a2d6",
-               "bytes_per_launch": 6089430235},
+               "bytes_per_launch": 6089412950},
 }
 
 
