@@ -343,3 +343,34 @@ def small_workload(seed: int, dims: Dims, n_layers: int, batch: int, seq: int,
     root = np.random.SeedSequence([BASE_SEED, 7, seed])
     return build_workload(f"small_{seed}", root, dims, n_layers, batch, seq, bit_choices,
                           n_absent, io_dtype=io_dtype, plan=plan)
+
+
+def make_every_term_matter(wl: Workload, seed: int, amp: float = 6.0) -> None:
+    """Rescale a workload in place so that every term of the layer moves its output.
+
+    With the configurations' recipe (weights N(0, 0.02), biases N(0, 0.02), LayerNorm gains
+    of exactly 1) the attention block changes the layer output by a few per cent only, and a
+    gain of 1 hides a dropped gain altogether.  Here all weights (codebooks and float32
+    shards) are multiplied by `amp`, gains become N(1, 0.3), shifts N(0, 0.3) and the six bias
+    vectors N(0, 0.2).  Input data only: what a layer computes from it is not this module's
+    business."""
+    rng = np.random.default_rng([BASE_SEED, 11, seed])
+    for layer in wl.shards:
+        for sh in layer:
+            if sh is None or sh.bitwidth == 0:
+                continue
+            if sh.bitwidth == 32:
+                sh.data *= np.float32(amp)
+            else:
+                sh.codebook *= np.float32(amp)
+            if sh.outlier_val is not None:
+                sh.outlier_val *= np.float32(amp)
+    d = wl.dims.d_model
+    for prm in wl.params:
+        for name in ("ln1_g", "ln2_g"):
+            getattr(prm, name)[:] = rng.normal(1.0, 0.3, d).astype(np.float32)
+        for name in ("ln1_b", "ln2_b"):
+            getattr(prm, name)[:] = rng.normal(0.0, 0.3, d).astype(np.float32)
+        for name in ("bq", "bk", "bv", "bo", "b1", "b2"):
+            v = getattr(prm, name)
+            v[:] = rng.normal(0.0, 0.2, v.shape).astype(np.float32)

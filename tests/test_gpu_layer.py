@@ -293,37 +293,20 @@ WIDE = S.Dims(128, 12, 64, 64, 1e-12)
 
 
 @pytest.mark.parametrize("prec,dims,B,L", [("f32", SMALL, 2, 19), ("mfma", MID, 1, 66), ("mfma", MID, 3, 100),
-                                           ("mfma", WIDE, 5, 128), ("mfma", WIDE, 9, 256)])
-def test_layernorm_gains_shifts_and_biases_that_matter(gpu, oracle_mod, prec, dims, B, L):
-    """The configurations' recipe has LayerNorm gains of exactly 1 and biases of 0.02: a kernel
-    that dropped a gain, swapped gain and shift or lost a bias would pass every other case.
-    Here gains are N(1, 0.3), shifts N(0, 0.3) and all six bias vectors N(0, 0.2), on every
-    route (float32; few-token, partial-sum and wide-tile matrix-core kernels)."""
+                                           ("mfma", WIDE, 5, 128), ("mfma", WIDE, 9, 256), ("mfma", MID, 2, 200),
+                                           ("mfma", MID, 2, 300)])
+def test_every_term_of_the_layer_matters(gpu, oracle_mod, prec, dims, B, L):
+    """With the configurations' recipe a kernel could leave out the score scale, bq or b1, or a
+    LayerNorm gain, and stay inside the binary16 tolerance (tests/test_oracle_layer.py measures
+    that on the reference).  Here weights are six times as large and gains, shifts and biases
+    are random, on every route: float32; few-token, partial-sum and wide-tile matrix-core
+    GEMMs; attention with the scores in registers (up to 128 and up to 256 keys) and with the
+    running maximum (300 keys)."""
     wl = S.small_workload(31000 + B * L, dims, 2, B, L, n_absent=1, io_dtype="f32" if prec == "f32" else "f16")
-    rng = np.random.default_rng(77 + B)
-    for prm in wl.params:
-        for name in ("ln1_g", "ln2_g"):
-            getattr(prm, name)[:] = rng.normal(1.0, 0.3, dims.d_model).astype(np.float32)
-        for name in ("ln1_b", "ln2_b"):
-            getattr(prm, name)[:] = rng.normal(0.0, 0.3, dims.d_model).astype(np.float32)
-        for name in ("bq", "bk", "bv", "bo", "b1", "b2"):
-            v = getattr(prm, name)
-            v[:] = rng.normal(0.0, 0.2, v.shape).astype(np.float32)
+    S.make_every_term_matter(wl, 77 + B)
     want = oracle_mod.model_forward(dims, wl.shards, wl.params, wl.x)
     got = run_gpu(gpu, wl, prec)
     assert rel_err(got, want) <= TOL[prec]
-
-
-@pytest.mark.parametrize("B,L,n_absent", [(15, 137, 0), (8, 512, 0), (4, 130, 9), (3, 171, 5)])
-def test_mfma_working_buffer_gemm_tile_shapes(gpu, oracle_mod, B, L, n_absent):
-    """Token counts and shard counts that make the working-buffer GEMM pick each of its tile
-    shapes (64 x 384 and 128 x 288 tiles for the Q/K/V projection, the two-group K split and
-    its fallback for an odd number of K tiles in the output projection), with ragged last
-    row tiles and column tiles that are not full."""
-    wl = S.small_workload(1000 + B * L, WIDE, 2, B, L, n_absent=n_absent, io_dtype="f16")
-    want = oracle_mod.model_forward(WIDE, wl.shards, wl.params, wl.x)
-    got = run_gpu(gpu, wl, "mfma")
-    assert rel_err(got, want) <= TOL["mfma"]
 
 
 def test_mfma_rows_beyond_2gib_of_activations(gpu):

@@ -7,6 +7,7 @@ float64, fed dense matrices assembled from the shards by numpy code local to
 this file), and identities the paper states for shards (independence of the
 vertical slices, any subset executes, mixed bitwidths are compatible).
 """
+import copy
 import json
 import math
 import os
@@ -307,3 +308,43 @@ def test_outlier_shard_equals_patched_full_precision_shard(oracle_mod):
     assert np.array_equal(y, y2)
     plain = [S.Shard(s.bitwidth, s.data, s.codebook) for s in shards]
     assert np.max(np.abs(y - oracle_mod.layer_forward(SMALL, plain, p, wl.x))) > 1e-4
+
+
+# ---------------------------------------------------------------- power of the binary16 parity cases
+
+def test_planted_mistakes_show_only_when_every_term_matters(oracle_mod):
+    """How much of a mistake the binary16 tolerance (2e-2) can see.  Mistakes are planted in the
+    reference's inputs: no score scale (Wq and bq times sqrt(dh) -- float32 shards only, so the
+    plan is all 32-bit), bq left out, b1 left out, a LayerNorm gain taken as 1.  With the
+    configurations' recipe the first three change the output by less than the tolerance, so
+    parity cases on that recipe alone could not tell; after S.make_every_term_matter every
+    one of them costs several times the tolerance.  (bk is absent on purpose: adding q.bk to
+    every score of a row leaves its softmax unchanged.)"""
+    dims = S.Dims(128, 4, 64, 64, 1e-12)
+    TOL16 = 2e-2
+
+    def effects(wl):
+        good = oracle_mod.layer_forward(dims, wl.shards[0], wl.params[0], wl.x)
+        rel = lambda y: float(np.max(np.abs(y - good)) / np.max(np.abs(good)))
+        out = {}
+        w2 = copy.deepcopy(wl)
+        n = dims.d_head * dims.d_model
+        for sh in w2.shards[0]:
+            sh.data[:n] *= np.float32(math.sqrt(dims.d_head))
+        w2.params[0].bq *= np.float32(math.sqrt(dims.d_head))
+        out["scale"] = rel(oracle_mod.layer_forward(dims, w2.shards[0], w2.params[0], w2.x))
+        for name, value in (("bq", 0.0), ("b1", 0.0), ("ln1_g", 1.0), ("ln2_g", 1.0)):
+            w2 = copy.deepcopy(wl)
+            getattr(w2.params[0], name)[:] = value
+            out[name] = rel(oracle_mod.layer_forward(dims, w2.shards[0], w2.params[0], w2.x))
+        return out
+
+    plan = np.array([[32, 32, 32, 32]])
+    recipe = effects(S.small_workload(5, dims, 1, 2, 100, plan=plan))
+    assert recipe["scale"] < TOL16 and recipe["bq"] < TOL16 and recipe["b1"] < TOL16
+    assert recipe["ln1_g"] == 0.0 and recipe["ln2_g"] == 0.0      # the recipe's gains are 1
+    wl = S.small_workload(5, dims, 1, 2, 100, plan=plan)
+    S.make_every_term_matter(wl, 3)
+    strong = effects(wl)
+    for name, e in strong.items():
+        assert e > 3 * TOL16, (name, e)
