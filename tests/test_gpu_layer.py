@@ -227,6 +227,24 @@ def test_mfma_config4_full_batch_sampled_sequences(gpu, oracle_mod):
         assert rel_err(got[b:b + 1], want) <= TOL["mfma"], b
 
 
+def test_mfma_full_size_every_term_matters(gpu, oracle_mod):
+    """BERT-base shapes in the launch configurations of configurations 4 (32 x 128 tokens,
+    wide-tile kernels) and 0 (1 x 128 tokens, few-token kernels), with weights three times as
+    large and random gains, shifts and biases: at this size dropping bq, bv, b1 or a gain moves
+    the reference by 10-40 %."""
+    wl = S.config4(n_layers=3)
+    S.make_every_term_matter(wl, 4, amp=3.0)
+    got = run_gpu(gpu, wl, "mfma")
+    assert np.all(np.isfinite(got))
+    for b in (0, 31):
+        want = oracle_mod.model_forward(wl.dims, wl.shards, wl.params, wl.x[b:b + 1])
+        assert rel_err(got[b:b + 1], want) <= TOL["mfma"], b
+    one = S.Workload("one_sequence", wl.dims, 1, wl.seq, wl.plan, wl.shards, wl.params, wl.x[5:6], wl.io_dtype)
+    got = run_gpu(gpu, one, "mfma")
+    want = oracle_mod.model_forward(wl.dims, wl.shards, wl.params, wl.x[5:6])
+    assert rel_err(got, want) <= TOL["mfma"]
+
+
 def test_mfma_rejects_unsupported_dims(gpu):
     torch, P, D = gpu
     assert P.sti_workspace_bytes(SMALL, 1, 8, P.STI_PREC_F16_MFMA) == 0
