@@ -350,10 +350,11 @@ sti_status sti_quantize_layer(const sti_dims *dims, const float *weights, int bi
  * Per-kernel timing (the counterpart of the paper's one-time hardware profiling
  * of computation delays, Section "Prerequisite: offline profiling").  Between
  * sti_profile_begin() and sti_profile_end() every kernel launch of the entry
- * points above is bracketed by two events on the caller's stream;
- * sti_profile_end() waits for them and returns, per kernel class, the number
- * of launches and the summed event-to-event time in milliseconds.  Process
- * wide, not re-entrant; meant for measurement runs, not for production calls.
+ * points above carries two events on the caller's stream that take the
+ * dispatch's own begin and end time stamps; sti_profile_end() waits for them
+ * and returns, per kernel class, the number of launches and the summed kernel
+ * time in milliseconds.  Process wide, not re-entrant; meant for measurement
+ * runs, not for production calls (nor for calls under stream capture).
  * ------------------------------------------------------------------------- */
 typedef enum {
     STI_K_DECODE = 0,

@@ -66,8 +66,9 @@ StagingRing &staging()
     return ring;
 }
 
-// Optional per-launch timing: while enabled, every kernel launch is bracketed
-// by two events on the caller's stream; sti_profile_end() sums them per class.
+// Optional per-launch timing: while enabled, every kernel launch of the entry points carries
+// two events that hold the dispatch's begin and end time stamps (see launch() in
+// sti_internal.hpp); sti_profile_end() sums them per class.
 class Profiler {
 public:
     bool enabled() const { return on_; }
@@ -78,26 +79,30 @@ public:
         on_ = true;
         return hipSuccess;
     }
-    hipError_t mark(int cls, hipStream_t stream, bool start)
+    // events for the next launch of class `cls` (nulls when timing is off)
+    hipError_t next(int cls, LaunchEvents *ev)
     {
         std::lock_guard<std::mutex> lock(mu_);
+        *ev = LaunchEvents{};
         if (!on_) return hipSuccess;
-        if (start) {
-            if (used_ == recs_.size()) {
-                Rec r;
-                r.cls = cls;
-                hipError_t e = hipEventCreate(&r.a);
-                if (e != hipSuccess) return e;
-                e = hipEventCreate(&r.b);
-                if (e != hipSuccess) return e;
-                recs_.push_back(r);
-            }
-            recs_[used_].cls = cls;
-            return hipEventRecord(recs_[used_].a, stream);
+        if (used_ == recs_.size()) {
+            Rec r;
+            hipError_t e = hipEventCreate(&r.a);
+            if (e != hipSuccess) return e;
+            e = hipEventCreate(&r.b);
+            if (e != hipSuccess) return e;
+            recs_.push_back(r);
         }
-        hipError_t e = hipEventRecord(recs_[used_].b, stream);
-        ++used_;
-        return e;
+        recs_[used_].cls = cls;
+        ev->start = recs_[used_].a;
+        ev->stop = recs_[used_].b;
+        return hipSuccess;
+    }
+    // the launch took the events: count it
+    void commit()
+    {
+        std::lock_guard<std::mutex> lock(mu_);
+        if (on_ && used_ < recs_.size()) ++used_;
     }
     hipError_t end(sti_profile *out)
     {
@@ -134,17 +139,28 @@ Profiler &profiler()
     return p;
 }
 
-// Launch `fn` (returns hipError_t), bracketed by profiling events when enabled.
+thread_local LaunchEvents pending_launch_events;
+
+// Run `fn` (one kernel launch through launch(); returns hipError_t) with timing events when enabled.
 template <typename F>
 hipError_t timed(int cls, hipStream_t stream, F fn)
 {
+    (void)stream;
     Profiler &pr = profiler();
     if (!pr.enabled()) return fn();
-    hipError_t e = pr.mark(cls, stream, true);
+    hipError_t e = pr.next(cls, &pending_launch_events);
     if (e != hipSuccess) return e;
     e = fn();
-    hipError_t e2 = pr.mark(cls, stream, false);
-    return e != hipSuccess ? e : e2;
+    if (pending_launch_events.start == nullptr) pr.commit();   // taken by the launch
+    pending_launch_events = LaunchEvents{};                      // (nothing was launched: dropped)
+    return e;
+}
+
+LaunchEvents take_launch_events()
+{
+    const LaunchEvents ev = pending_launch_events;
+    pending_launch_events = LaunchEvents{};
+    return ev;
 }
 
 inline ShardDesc make_desc(const sti_shard &s, int tag)

@@ -252,24 +252,24 @@ hipError_t launch_attention_mfma(const void *qkv, void *ctx, int B, int L, int m
     if (small_wg) {
         dim3 grid((L + 63) / 64, m, B);
         if (Lp <= 128)
-            attention_mfma_kernel<2, 4><<<grid, dim3(128), lds, stream>>>((const _Float16 *)qkv,
+            launch((attention_mfma_kernel<2, 4>), grid, dim3(128), lds, stream, (const _Float16 *)qkv,
                                                                           (_Float16 *)ctx, L, Lp, m);
         else if (Lp <= 256)
-            attention_mfma_kernel<2, 8><<<grid, dim3(128), lds, stream>>>((const _Float16 *)qkv,
+            launch((attention_mfma_kernel<2, 8>), grid, dim3(128), lds, stream, (const _Float16 *)qkv,
                                                                           (_Float16 *)ctx, L, Lp, m);
         else
-            attention_mfma_kernel<2, 0><<<grid, dim3(128), lds, stream>>>((const _Float16 *)qkv,
+            launch((attention_mfma_kernel<2, 0>), grid, dim3(128), lds, stream, (const _Float16 *)qkv,
                                                                           (_Float16 *)ctx, L, Lp, m);
     } else {
         dim3 grid((L + 127) / 128, m, B);
         if (Lp <= 128)
-            attention_mfma_kernel<4, 4><<<grid, dim3(256), lds, stream>>>((const _Float16 *)qkv,
+            launch((attention_mfma_kernel<4, 4>), grid, dim3(256), lds, stream, (const _Float16 *)qkv,
                                                                           (_Float16 *)ctx, L, Lp, m);
         else if (Lp <= 256)
-            attention_mfma_kernel<4, 8><<<grid, dim3(256), lds, stream>>>((const _Float16 *)qkv,
+            launch((attention_mfma_kernel<4, 8>), grid, dim3(256), lds, stream, (const _Float16 *)qkv,
                                                                           (_Float16 *)ctx, L, Lp, m);
         else
-            attention_mfma_kernel<4, 0><<<grid, dim3(256), lds, stream>>>((const _Float16 *)qkv,
+            launch((attention_mfma_kernel<4, 0>), grid, dim3(256), lds, stream, (const _Float16 *)qkv,
                                                                           (_Float16 *)ctx, L, Lp, m);
     }
     return hipGetLastError();

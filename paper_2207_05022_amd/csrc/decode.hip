@@ -204,12 +204,12 @@ hipError_t launch_typed(const ShardDesc *table, const InlineShardTable *inline_t
     typedef typename Out::bits_t bits_t;
     if (table) {
         TablePtr t{table};
-        decode_kernel<Out, TablePtr><<<dim3((uint32_t)blocks), dim3(kThreads), 0, stream>>>(
+        launch((decode_kernel<Out, TablePtr>), dim3((uint32_t)blocks), dim3(kThreads), 0, stream, 
             t, n, (uint32_t)chunks, (bits_t *)out, vec_ok);
     } else {
         TableInline t;
         t.t = *inline_table;
-        decode_kernel<Out, TableInline><<<dim3((uint32_t)blocks), dim3(kThreads), 0, stream>>>(
+        launch((decode_kernel<Out, TableInline>), dim3((uint32_t)blocks), dim3(kThreads), 0, stream, 
             t, n, (uint32_t)chunks, (bits_t *)out, vec_ok);
     }
     return hipGetLastError();
@@ -381,7 +381,7 @@ hipError_t launch_decode_tiled(const InlineShardTable &table, int n_shards, int 
     const int64_t cells = wsh / 2048 * n_shards;
     if (cells == 0) return hipSuccess;
     if (d % 64 || dh % 64 || f % 64 || cells > 0x7FFFFFF0) return hipErrorInvalidValue;
-    decode_tiled_kernel<TableInline><<<dim3((uint32_t)((cells + 3) / 4)), dim3(256), 0, stream>>>(
+    launch((decode_tiled_kernel<TableInline>), dim3((uint32_t)((cells + 3) / 4)), dim3(256), 0, stream, 
         TableInline{table}, (int)cells, d, dh, f, (uint8_t *)out);
     return hipGetLastError();
 }
@@ -393,7 +393,7 @@ hipError_t launch_decode_tiled_table(const ShardDesc *device_table, int n_shards
     const int64_t cells = wsh / 2048 * n_shards;
     if (cells == 0) return hipSuccess;
     if (d % 64 || dh % 64 || f % 64 || cells > 0x7FFFFFF0) return hipErrorInvalidValue;
-    decode_tiled_kernel<TablePtr><<<dim3((uint32_t)((cells + 3) / 4)), dim3(256), 0, stream>>>(
+    launch((decode_tiled_kernel<TablePtr>), dim3((uint32_t)((cells + 3) / 4)), dim3(256), 0, stream, 
         TablePtr{device_table}, (int)cells, d, dh, f, (uint8_t *)out);
     return hipGetLastError();
 }

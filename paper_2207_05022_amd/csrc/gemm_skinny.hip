@@ -220,7 +220,7 @@ hipError_t launch_ra(const GemmProblem &p, const GemmBlocks &blocks, int N, int 
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    gemm_skinny_kernel<RA><<<grid, dim3(NW * 64), sizeof(SkinnySmem<RA>), stream>>>(p, blocks, k_splits,
+    launch((gemm_skinny_kernel<RA>), grid, dim3(NW * 64), sizeof(SkinnySmem<RA>), stream, p, blocks, k_splits,
                                                                               partial_stride);
     return hipGetLastError();
 }

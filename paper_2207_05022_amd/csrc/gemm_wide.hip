@@ -381,7 +381,7 @@ hipError_t launch_shape(const GemmProblem &p, const GemmBlocks &blocks, int N, h
     const int total = ((N + BN - 1) / BN) * ((p.T + BM - 1) / BM);
     const bool n_split = (KIND == GEMM_QKV || KIND == GEMM_FFN_UP);
     dim3 grid(((total + 7) / 8) * 8, (!n_split && p.k_splits > 1) ? p.k_splits : 1);
-    gemm_wide_kernel<KIND, RA, NW, KS><<<grid, dim3(NW * KS * 64), lds, stream>>>(p, blocks);
+    launch((gemm_wide_kernel<KIND, RA, NW, KS>), grid, dim3(NW * KS * 64), lds, stream, p, blocks);
     return hipGetLastError();
 }
 

@@ -161,7 +161,7 @@ hipError_t launch_gemm_f32(const GemmProblem &p, const GemmBlocks &blocks, hipSt
     const int N = n_split ? p.n_blocks * p.block_rows : p.block_rows;
     if (p.T <= 0 || N <= 0) return hipSuccess;
     dim3 grid((N + BN - 1) / BN, (p.T + BM - 1) / BM);
-    gemm_f32_kernel<<<grid, dim3(256), 0, stream>>>(p, blocks);
+    launch(gemm_f32_kernel, grid, dim3(256), 0, stream, p, blocks);
     return hipGetLastError();
 }
 
@@ -171,7 +171,7 @@ hipError_t launch_attention_f32(const float *qkv, float *ctx, int B, int L, int 
     if (B <= 0 || L <= 0 || m <= 0) return hipSuccess;
     dim3 grid((L + 3) / 4, m, B);
     size_t lds = (size_t)4 * (L + dh) * sizeof(float);
-    attention_f32_kernel<<<grid, dim3(256), lds, stream>>>(qkv, ctx, L, m, dh);
+    launch(attention_f32_kernel, grid, dim3(256), lds, stream, qkv, ctx, L, m, dh);
     return hipGetLastError();
 }
 

@@ -233,13 +233,13 @@ hipError_t convert_from(const void *src, void *dst, sti_dtype dst_dtype, uint64_
     typedef typename Elem<SRC>::type S;
     switch (dst_dtype) {
         case STI_F32:
-            convert_kernel<SRC, STI_F32><<<grid, 256, 0, stream>>>((const S *)src, (float *)dst, n);
+            launch((convert_kernel<SRC, STI_F32>), grid, dim3(256), 0, stream, (const S *)src, (float *)dst, n);
             break;
         case STI_F16:
-            convert_kernel<SRC, STI_F16><<<grid, 256, 0, stream>>>((const S *)src, (_Float16 *)dst, n);
+            launch((convert_kernel<SRC, STI_F16>), grid, dim3(256), 0, stream, (const S *)src, (_Float16 *)dst, n);
             break;
         case STI_BF16:
-            convert_kernel<SRC, STI_BF16><<<grid, 256, 0, stream>>>((const S *)src, (uint16_t *)dst, n);
+            launch((convert_kernel<SRC, STI_BF16>), grid, dim3(256), 0, stream, (const S *)src, (uint16_t *)dst, n);
             break;
     }
     return hipGetLastError();
@@ -256,11 +256,11 @@ void launch_ln_typed(const float *pre, int n_partials, int64_t partial_stride, c
     dim3 grid((T + 3) / 4);
     // many rows: 16 lanes per row (16 rows per workgroup); few rows: a whole wave per row
     if (vec && T >= 2048 && d <= 1024)
-        layernorm_vec_kernel<DT, 32, 8><<<dim3((T + 7) / 8), 256, 0, stream>>>(pre, n_partials, partial_stride, bias, (const _Float16 *)resid, (O *)y, g, b, T, d, eps);
+        launch((layernorm_vec_kernel<DT, 32, 8>), dim3((T + 7) / 8), dim3(256), 0, stream, pre, n_partials, partial_stride, bias, (const _Float16 *)resid, (O *)y, g, b, T, d, eps);
     else if (vec)
-        layernorm_vec_kernel<DT, 64, 8><<<grid, 256, 0, stream>>>(pre, n_partials, partial_stride, bias, (const _Float16 *)resid, (O *)y, g, b, T, d, eps);
+        launch((layernorm_vec_kernel<DT, 64, 8>), grid, dim3(256), 0, stream, pre, n_partials, partial_stride, bias, (const _Float16 *)resid, (O *)y, g, b, T, d, eps);
     else
-        layernorm_kernel<DT><<<grid, 256, 0, stream>>>(pre, n_partials, partial_stride, bias, (const _Float16 *)resid, (O *)y, g, b, T, d, eps);
+        launch((layernorm_kernel<DT>), grid, dim3(256), 0, stream, pre, n_partials, partial_stride, bias, (const _Float16 *)resid, (O *)y, g, b, T, d, eps);
 }
 
 hipError_t launch_layernorm(const float *pre, int n_partials, int64_t partial_stride,
@@ -289,9 +289,9 @@ hipError_t launch_layernorm_f16in(const void *pre_f16, void *y, sti_dtype out_dt
     dim3 grid((T + 3) / 4);
     const _Float16 *p = (const _Float16 *)pre_f16;
     switch (out_dtype) {
-        case STI_F32: layernorm_f16in_kernel<STI_F32><<<grid, 256, 0, stream>>>(p, (float *)y, g, b, T, d, eps); break;
-        case STI_F16: layernorm_f16in_kernel<STI_F16><<<grid, 256, 0, stream>>>(p, (_Float16 *)y, g, b, T, d, eps); break;
-        case STI_BF16: layernorm_f16in_kernel<STI_BF16><<<grid, 256, 0, stream>>>(p, (uint16_t *)y, g, b, T, d, eps); break;
+        case STI_F32: launch((layernorm_f16in_kernel<STI_F32>), grid, dim3(256), 0, stream, p, (float *)y, g, b, T, d, eps); break;
+        case STI_F16: launch((layernorm_f16in_kernel<STI_F16>), grid, dim3(256), 0, stream, p, (_Float16 *)y, g, b, T, d, eps); break;
+        case STI_BF16: launch((layernorm_f16in_kernel<STI_BF16>), grid, dim3(256), 0, stream, p, (uint16_t *)y, g, b, T, d, eps); break;
     }
     return hipGetLastError();
 }

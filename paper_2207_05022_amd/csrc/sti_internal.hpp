@@ -1,6 +1,7 @@
 // Internal declarations shared by the translation units of libsti (HIP, gfx950 only).
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 #include "sti.h"
 
@@ -135,5 +136,25 @@ hipError_t launch_layernorm_f16in(const void *pre_f16, void *y, sti_dtype out_dt
 // elementwise conversion between activation types
 hipError_t launch_convert(const void *src, sti_dtype src_dtype, void *dst, sti_dtype dst_dtype,
                           uint64_t n, hipStream_t stream);
+
+// Kernel launches of the entry points go through launch(): while per-kernel timing is on
+// (sti_profile_begin), the launch carries the two events the profiler handed out, which then
+// hold the dispatch's own begin and end time stamps -- the same stamps a kernel trace reads.
+// (Two events recorded around a launch read about 2.5 us more than the kernel lasts: the
+// record-to-start latency.)  Without timing it is an ordinary launch.
+struct LaunchEvents {
+    hipEvent_t start = nullptr, stop = nullptr;
+};
+LaunchEvents take_launch_events();   // api.hip; nulls unless a timed launch is pending on this thread
+
+template <typename... P, typename... A>
+inline void launch(void (*kernel)(P...), dim3 grid, dim3 block, size_t lds_bytes, hipStream_t stream, A... args)
+{
+    const LaunchEvents ev = take_launch_events();
+    if (ev.start)
+        hipExtLaunchKernelGGL(kernel, grid, block, (uint32_t)lds_bytes, stream, ev.start, ev.stop, 0, (P)args...);
+    else
+        hipLaunchKernelGGL(kernel, grid, block, (uint32_t)lds_bytes, stream, (P)args...);
+}
 
 }  // namespace sti
