@@ -384,3 +384,44 @@ def test_model_forward_can_be_stream_captured(gpu, oracle_mod):
         P.sti_model_forward(MID, store, params, wl.plan, x, scratch, prec, ws)   # eager work between replays
         torch.cuda.synchronize()
         assert torch.equal(scratch, y_eager)
+
+
+@pytest.mark.parametrize("B,L", [(1, 64), (4, 128)])   # few-token route / working-buffer route
+def test_per_kernel_timing_counts_every_launch_and_changes_nothing(gpu, B, L):
+    """sti_profile_begin/end: the launches carry timing events; the counts per kernel class
+    are those of the route, every class with launches has a positive time, the sum of the
+    kernel times is below the wall time of the forward, and the output is bit for bit what an
+    untimed call gives."""
+    import time
+    torch, P, D = gpu
+    n_layers = 3
+    wl = S.small_workload(4100 + L, MID, n_layers, B, L, io_dtype="f16")
+    shards, params, x = D.upload_workload(wl)
+    store = P.make_store(D.store_from_plan(shards))
+    prec = P.STI_PREC_F16_MFMA
+    ws = torch.empty(P.sti_model_workspace_bytes(MID, n_layers, B, L, prec), dtype=torch.uint8, device="cuda")
+    y0 = torch.empty_like(x)
+    P.sti_model_forward(MID, store, params, wl.plan, x, y0, prec, ws)
+    torch.cuda.synchronize()
+    y1 = torch.full_like(x, float("nan"))
+    P.sti_profile_begin()
+    t0 = time.perf_counter()
+    P.sti_model_forward(MID, store, params, wl.plan, x, y1, prec, ws)
+    prof = P.sti_profile_end()          # waits for the events
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    torch.cuda.synchronize()
+    assert torch.equal(y0, y1)
+    count = {k: v[0] for k, v in prof.items()}
+    for k in ("gemm_qkv", "attention", "gemm_out", "gemm_ffn_up", "gemm_ffn_down"):
+        assert count[k] == n_layers, (k, count)
+    assert count["layernorm"] == 2 * n_layers
+    few_tokens = B * L <= 128
+    assert (count["decode"] == 0) if few_tokens else (1 <= count["decode"] <= n_layers)
+    total = 0.0
+    for k, (n, ms) in prof.items():
+        assert (ms > 0.0) == (n > 0), (k, n, ms)
+        total += ms
+    assert total < wall_ms
+    # a second begin/end pair starts from zero
+    P.sti_profile_begin()
+    assert all(n == 0 for n, _ in P.sti_profile_end().values())
