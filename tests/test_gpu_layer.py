@@ -228,10 +228,10 @@ def test_mfma_config4_full_batch_sampled_sequences(gpu, oracle_mod):
 
 
 def test_mfma_full_size_every_term_matters(gpu, oracle_mod):
-    """BERT-base shapes in the launch configurations of configurations 4 (32 x 128 tokens,
-    wide-tile kernels) and 0 (1 x 128 tokens, few-token kernels), with weights three times as
-    large and random gains, shifts and biases: at this size dropping bq, bv, b1 or a gain moves
-    the reference by 10-40 %."""
+    """The shapes and launch configurations of configurations 4 (32 x 128 tokens, wide-tile
+    kernels), 0 (1 x 128 tokens, few-token kernels) and 3, with weights three times as large
+    and random gains, shifts and biases: at this size dropping bq, bv, b1 or a gain moves the
+    reference by 10-40 %."""
     wl = S.config4(n_layers=3)
     S.make_every_term_matter(wl, 4, amp=3.0)
     got = run_gpu(gpu, wl, "mfma")
@@ -242,6 +242,12 @@ def test_mfma_full_size_every_term_matters(gpu, oracle_mod):
     one = S.Workload("one_sequence", wl.dims, 1, wl.seq, wl.plan, wl.shards, wl.params, wl.x[5:6], wl.io_dtype)
     got = run_gpu(gpu, one, "mfma")
     want = oracle_mod.model_forward(wl.dims, wl.shards, wl.params, wl.x[5:6])
+    assert rel_err(got, want) <= TOL["mfma"]
+    # configuration 3's shape (d_model 1024, 12 of 16 shards, 256 tokens: K split over workgroups)
+    wl3 = S.config3(n_layers=2)
+    S.make_every_term_matter(wl3, 5, amp=3.0)
+    got = run_gpu(gpu, wl3, "mfma")
+    want = oracle_mod.model_forward(wl3.dims, wl3.shards, wl3.params, wl3.x)
     assert rel_err(got, want) <= TOL["mfma"]
 
 
