@@ -333,6 +333,18 @@ def test_every_term_of_the_layer_matters(gpu, oracle_mod, prec, dims, B, L):
     assert rel_err(got, want) <= TOL[prec]
 
 
+def test_mfma_many_column_tiles_take_the_band_order(gpu, oracle_mod):
+    """More than 12 column tiles (here 32 shards: 16 column tiles for Q/K/V, 22 for FFN1) make the
+    wide-tile GEMM walk its tiles in bands of 8 row tiles; 11 row tiles leave a short last band
+    and 1400 tokens a ragged last row tile."""
+    dims = S.Dims(128, 32, 64, 256, 1e-12)
+    wl = S.small_workload(2048, dims, 1, 7, 200, n_absent=3, io_dtype="f16")
+    S.make_every_term_matter(wl, 9, amp=3.0)
+    want = oracle_mod.model_forward(dims, wl.shards, wl.params, wl.x)
+    got = run_gpu(gpu, wl, "mfma")
+    assert rel_err(got, want) <= TOL["mfma"]
+
+
 def test_mfma_rows_beyond_2gib_of_activations(gpu):
     """350,000 tokens: the FFN activations (T x 3072 binary16) pass 2 GiB, so row addresses need
     64 bits.  Sequences are independent, so the first and the last sequence of the big batch
