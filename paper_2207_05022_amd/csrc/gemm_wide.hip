@@ -71,7 +71,7 @@ constexpr size_t wide_lds_bytes()
 // each take one half of K for the same tile, with A stages of their own; the second group
 // hands its accumulators over through LDS at the end.  Twice the waves per compute unit for
 // a tile count that is fixed by the output size.
-template <int KIND, int RA, int NW, int KS>
+template <int KIND, int RA, int NW, int KS, bool EARLY>
 __global__ __launch_bounds__(NW * KS * 64, 3) void gemm_wide_kernel(GemmProblem p, GemmBlocks blocks)
 {
     constexpr int BM = RA * 32, BN = NW * 32, NT = NW * KS * 64, NTH = NW * 64;
@@ -196,6 +196,46 @@ __global__ __launch_bounds__(NW * KS * 64, 3) void gemm_wide_kernel(GemmProblem 
                      : "=&v"(dst[0]), "=&v"(dst[1]), "=&v"(dst[2]), "=&v"(dst[3]) : "v"(lane16), "s"(q) : "memory");
     };
 #define STI_WAIT_LOADS(n) asm volatile("s_waitcnt vmcnt(" #n ")" ::: "memory")
+    // EARLY (64-row tiles of the d_model-wide projections, K not split over workgroups): what
+    // the epilogue adds (bias and residual rows) is asked for before the K loop: asked for in
+    // the epilogue, these loads cost a whole round trip (3-4 thousand clocks of a 20-50 thousand
+    // clock kernel).  They are the oldest loads in flight, so the first wait of the K loop
+    // covers them.  (A variant of its own: with K split over workgroups nothing is added here.)
+    constexpr bool PRE = EARLY;
+    static_assert(!EARLY || (!n_split && RA <= 2), "early operands: 64-row tiles of OUT / FFN_DOWN");
+    const _Float16 *R = (const _Float16 *)p.resid;
+    f32x4 bias[2][2];
+    u32x4 resv[PRE ? RA : 1][2];
+    auto load_epilogue_operands = [&]() {
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            const int c = 16 * q + 8 * g;     // first column of the piece inside the wave's strip
+            const float *bp;
+            if constexpr (KIND == GEMM_QKV) {
+                const int nrow = nrow0 + c;
+                const int which = nrow / p.d_head, e0 = nrow - which * p.d_head;
+                bp = (which == 0 ? p.bias0 : (which == 1 ? p.bias1 : p.bias2)) + blocks.b[nblk].shard * p.d_head + e0;
+            } else if constexpr (KIND == GEMM_FFN_UP) {
+                bp = p.bias0 + blocks.b[nblk].shard * p.block_rows + nrow0 + c;
+            } else {
+                bp = p.bias0 + nw + c;
+            }
+            bias[q][0] = *(const f32x4 *)bp;
+            bias[q][1] = *(const f32x4 *)(bp + 4);
+        }
+        if constexpr (PRE) {
+#pragma unroll
+            for (int i = 0; i < RA; ++i) {
+                const int m = m0 + i * 32 + lr;
+#pragma unroll
+                for (int q = 0; q < 2; ++q) {
+                    u32x4 v = {0, 0, 0, 0};
+                    if (m < p.T) v = *(const u32x4 *)(R + (int64_t)m * p.ldr + nw + 16 * q + 8 * g);
+                    resv[i][q] = v;
+                }
+            }
+        }
+    };
     auto step = [&](int kt, u32x4 (&bcur)[4], u32x4 (&bnew)[4]) {
         // the weight fragments and the A stage of tile kt have landed (the barrier below is a
         // scheduling boundary: no MFMA of this step is placed above the wait) ...
@@ -237,6 +277,7 @@ __global__ __launch_bounds__(NW * KS * 64, 3) void gemm_wide_kernel(GemmProblem 
         }
     };
     static_assert(FPW <= 2, "the hand-written waits cover up to two A fetches per wave");
+    if (PRE && half == 0) load_epilogue_operands();
     if (nkt > 0) issue(0, bw[0]);
     if (nkt > 1) issue(1, bw[1]);
     for (int kt = 0; kt < nkt; kt += 3) {
@@ -252,24 +293,9 @@ __global__ __launch_bounds__(NW * KS * 64, 3) void gemm_wide_kernel(GemmProblem 
     // 8 consecutive columns 16q + 8g .. +8 of its row: one 16-byte piece of the output row.
     constexpr int LDT = BN + 8;   // padded row of the staged tile (halves): conflict-free 16-byte writes
     _Float16 *tile_out = (_Float16 *)smem_raw;
-    const _Float16 *R = (const _Float16 *)p.resid;
-    f32x4 bias[2][2];
-#pragma unroll
-    for (int q = 0; q < 2; ++q) {
-        const int c = 16 * q + 8 * g;     // first column of the piece inside the wave's strip
-        const float *bp;
-        if constexpr (KIND == GEMM_QKV) {
-            const int nrow = nrow0 + c;
-            const int which = nrow / p.d_head, e0 = nrow - which * p.d_head;
-            bp = (which == 0 ? p.bias0 : (which == 1 ? p.bias1 : p.bias2)) + blocks.b[nblk].shard * p.d_head + e0;
-        } else if constexpr (KIND == GEMM_FFN_UP) {
-            bp = p.bias0 + blocks.b[nblk].shard * p.block_rows + nrow0 + c;
-        } else {
-            bp = p.bias0 + nw + c;
-        }
-        bias[q][0] = *(const f32x4 *)bp;
-        bias[q][1] = *(const f32x4 *)(bp + 4);
-    }
+    // (also when K is split over workgroups and nothing is added here: leaving these loads out
+    //  made those launches 2 % slower, measured twice)
+    if (!PRE) load_epilogue_operands();
     __syncthreads();   // every wave is done with the A stages
     if constexpr (KS == 2) {
         // second K group -> LDS -> first K group (same lane, same registers)
@@ -324,7 +350,10 @@ __global__ __launch_bounds__(NW * KS * 64, 3) void gemm_wide_kernel(GemmProblem 
     for (int i = 0; i < RA; ++i) {
         const int row = i * 32 + lr;          // row inside the tile
         half8 res[2];
-        if constexpr (!n_split) {
+        if constexpr (PRE) {
+            res[0] = __builtin_bit_cast(half8, resv[i][0]);
+            res[1] = __builtin_bit_cast(half8, resv[i][1]);
+        } else if constexpr (!n_split) {
             const int m = m0 + row;
 #pragma unroll
             for (int q = 0; q < 2; ++q) {
@@ -378,14 +407,27 @@ __global__ __launch_bounds__(NW * KS * 64, 3) void gemm_wide_kernel(GemmProblem 
     }
 }
 
+template <int KIND, int RA, int NW, int KS, bool EARLY>
+hipError_t launch_variant(const GemmProblem &p, const GemmBlocks &blocks, int N, hipStream_t stream);
+
 template <int KIND, int RA, int NW, int KS>
 hipError_t launch_shape(const GemmProblem &p, const GemmBlocks &blocks, int N, hipStream_t stream)
+{
+    constexpr bool n_split = (KIND == GEMM_QKV || KIND == GEMM_FFN_UP);
+    if constexpr (!n_split && RA <= 2) {
+        if (p.k_splits <= 1) return launch_variant<KIND, RA, NW, KS, true>(p, blocks, N, stream);
+    }
+    return launch_variant<KIND, RA, NW, KS, false>(p, blocks, N, stream);
+}
+
+template <int KIND, int RA, int NW, int KS, bool EARLY>
+hipError_t launch_variant(const GemmProblem &p, const GemmBlocks &blocks, int N, hipStream_t stream)
 {
     constexpr int BM = RA * 32, BN = NW * 32;
     constexpr size_t lds = wide_lds_bytes<RA, NW, KS>();
     static bool attr_set = false;   // per instantiation
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)gemm_wide_kernel<KIND, RA, NW, KS>,
+        hipError_t e = hipFuncSetAttribute((const void *)gemm_wide_kernel<KIND, RA, NW, KS, EARLY>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         attr_set = true;
@@ -393,7 +435,7 @@ hipError_t launch_shape(const GemmProblem &p, const GemmBlocks &blocks, int N, h
     const int total = ((N + BN - 1) / BN) * ((p.T + BM - 1) / BM);
     const bool n_split = (KIND == GEMM_QKV || KIND == GEMM_FFN_UP);
     dim3 grid(((total + 7) / 8) * 8, (!n_split && p.k_splits > 1) ? p.k_splits : 1);
-    launch((gemm_wide_kernel<KIND, RA, NW, KS>), grid, dim3(NW * KS * 64), lds, stream, p, blocks);
+    launch((gemm_wide_kernel<KIND, RA, NW, KS, EARLY>), grid, dim3(NW * KS * 64), lds, stream, p, blocks);
     return hipGetLastError();
 }
 
