@@ -129,3 +129,23 @@ def test_outliers_with_device_table(gpu, oracle_mod):
               for k in rng.choice([2, 3, 4, 5, 6], size=70)]
     got = run_decode(gpu, shards, n, "f16")
     assert np.array_equal(got, oracle_bits(oracle_mod, shards, n, "f16"))
+
+
+def test_random_sizes_bitwidths_and_dictionaries(gpu, oracle_mod):
+    """Sixty seeded random calls: 1-90 shards of random bitwidths, 1-150,000 weights per shard,
+    any of the three output types, outlier dictionaries on a random subset."""
+    rng = np.random.default_rng(20240608)
+    for case in range(60):
+        n = int(rng.choice([int(rng.integers(1, 300)), int(rng.integers(300, 20000)), int(rng.integers(20000, 150000))]))
+        n_shards = int(rng.choice([1, 2, 5, 17, 64, 65, 90])) if n < 20000 else int(rng.integers(1, 9))
+        dtype = str(rng.choice(["f16", "f32", "bf16"]))
+        shards = []
+        for _ in range(n_shards):
+            k = int(rng.choice([2, 3, 4, 5, 6, 32]))
+            sh = S.make_shard(rng, n, k)
+            if k != 32 and rng.random() < 0.4 and n >= 8:
+                sh = S.add_outliers(rng, sh, n, fraction=float(rng.choice([0.001, 0.01, 0.1])))
+            shards.append(sh)
+        got = run_decode(gpu, shards, n, dtype)
+        want = oracle_bits(oracle_mod, shards, n, dtype)
+        assert np.array_equal(got, want), (case, n, n_shards, dtype)
