@@ -153,6 +153,30 @@ def test_f32_config3(gpu, oracle_mod):
     assert rel_err(got, want) <= TOL["f32"]
 
 
+def test_f32_random_shapes(gpu, oracle_mod):
+    """Thirty seeded random shapes on the float32 path, which takes any dimensions: d_model 8-128,
+    1-8 shards of 4-64 wide heads and 4-64 FFN neurons, 1-200 keys, 1-3 layers, float32 or
+    binary16 activations at the boundary."""
+    rng = np.random.default_rng(777)
+    for case in range(30):
+        M = int(rng.integers(1, 9))
+        dh = int(rng.choice([4, 8, 12, 16, 20, 32, 64]))
+        f = int(rng.choice([4, 8, 24, 32, 40, 64]))
+        d = int(rng.choice([8, 16, 24, 40, 48, 72, 96, 128]))
+        dims = S.Dims(d, M, dh, f, 1e-12)
+        L = int(rng.integers(1, 200))
+        B = int(rng.integers(1, 6))
+        n_abs = int(rng.integers(0, M)) if M > 1 else 0
+        n_layers = int(rng.choice([1, 2, 3]))
+        io = str(rng.choice(["f32", "f16"]))
+        wl = S.small_workload(12000 + case, dims, n_layers, B, L, n_absent=n_abs, io_dtype=io)
+        S.make_every_term_matter(wl, case, amp=float(rng.choice([1.0, 4.0])))
+        want = oracle_mod.model_forward(dims, wl.shards, wl.params, wl.x)
+        got = run_gpu(gpu, wl, "f32")
+        tol = TOL["f32"] if io == "f32" else 2e-3    # binary16 output: half an ulp of the largest value
+        assert rel_err(got, want) <= tol, (case, d, M, dh, f, B, L, n_abs, n_layers, io)
+
+
 def test_empty_batch_and_zero_layers(gpu):
     torch, P, D = gpu
     wl = S.small_workload(3, SMALL, 1, 1, 4)
