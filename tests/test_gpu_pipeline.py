@@ -259,3 +259,35 @@ def test_pipeline_empty_batch_and_zero_layers(gpu):
     torch.cuda.synchronize()
     assert torch.equal(y, rig.x) and st["bytes_copied"] == 0
     rig.pipe.close()
+
+
+def test_pipeline_random_models_buffers_and_slots(gpu):
+    """Twenty seeded random set-ups (precision, 1-6 layers, tokens, absent shards, preload buffer
+    from none to more than everything, 2-8 staging slots, pinned or ordinary host memory): cold,
+    warm and unsynchronised back-to-back calls give the bits of sti_model_forward, and the byte
+    counts are those of the longest prefix that fits the buffer."""
+    torch = gpu[0]
+    rng = np.random.default_rng(4711)
+    for case in range(20):
+        prec = str(rng.choice(["f32", "mfma"]))
+        dims = SMALL if prec == "f32" else MID
+        n_layers = int(rng.integers(1, 7))
+        B, L = int(rng.integers(1, 6)), int(rng.integers(1, 200))
+        wl = S.small_workload(5000 + case, dims, n_layers, B, L, n_absent=int(rng.integers(0, dims.n_heads)))
+        total = sum(plan_bytes(dims, wl.plan))
+        preload = int(rng.choice([0, total // 7, total // 2, total, total + 4096]))
+        rig = Rig(gpu, wl, prec, preload_bytes=preload, host_data=bool(rng.random() < 0.8),
+                  slots=int(rng.integers(2, 9)))
+        ref = rig.reference()
+        n_res, b_res = expected_resident(dims, wl.plan, preload)
+        y, st = rig.run()
+        assert torch.equal(y, ref), case
+        assert st["bytes_copied"] == total and st["shards_hit"] == 0, case
+        assert st["shards_preloaded"] == n_res and st["bytes_resident"] == b_res, case
+        y, st = rig.run()
+        assert torch.equal(y, ref), case
+        assert st["shards_hit"] == n_res and st["bytes_copied"] == total - b_res, case
+        y3, _ = rig.run(sync=False)
+        y4, _ = rig.run()
+        assert torch.equal(y3, ref) and torch.equal(y4, ref), case
+        rig.pipe.close()
