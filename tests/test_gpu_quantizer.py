@@ -133,3 +133,29 @@ def test_quantizer_duplicates_zeros_and_truncated_dictionary():
         keep = min(n, 4)
         assert np.array_equal(g["pos"][s, :keep].cpu().numpy().view(np.uint32), q["outlier_pos"][s][:keep])
     assert cnt[1] >= 10 > 4
+
+
+def test_quantizer_random_layers_and_distributions():
+    """Twenty-four seeded random layers: 1-12 shards, three widths, every bitwidth; Gaussian,
+    heavy-tailed, rounded (many duplicates), uniform, far from zero, and minute weights."""
+    rng = np.random.default_rng(31337)
+    for case in range(24):
+        M = int(rng.choice([1, 2, 3, 4, 8, 12]))
+        dims = S.Dims(int(rng.choice([64, 128, 192])), M, 64, int(rng.choice([64, 128, 256])), 1e-12)
+        k = int(rng.choice([2, 3, 4, 5, 6]))
+        kind = str(rng.choice(["gauss", "tails", "dups", "uniform", "shifted", "tiny"]))
+        wsh = dims.weights_per_shard
+        if kind == "gauss":
+            w = rng.normal(0, 0.03, (M, wsh))
+        elif kind == "tails":
+            w = layer_weights(case, dims, sigma=float(rng.choice([0.01, 0.05])), tail=float(rng.choice([0.0005, 0.003])))
+        elif kind == "dups":
+            w = np.round(rng.normal(0, 0.03, (M, wsh)), int(rng.choice([2, 3])))
+        elif kind == "uniform":
+            w = rng.uniform(-0.1, 0.1, (M, wsh))
+        elif kind == "shifted":
+            w = rng.normal(0.5, 0.02, (M, wsh))
+        else:
+            w = rng.normal(0, 1e-6, (M, wsh))
+        w = np.asarray(w, dtype=np.float32)
+        check_against_reference(dims, w, k, run_gpu(dims, w, k, max_out=4096))
