@@ -149,3 +149,45 @@ def test_random_sizes_bitwidths_and_dictionaries(gpu, oracle_mod):
         got = run_decode(gpu, shards, n, dtype)
         want = oracle_bits(oracle_mod, shards, n, dtype)
         assert np.array_equal(got, want), (case, n, n_shards, dtype)
+
+
+def test_config1_full_size_sampled_shards(gpu, oracle_mod):
+    """The whole decode stream of configuration 1 (4221 BERT-base shards, 1 GiB of packed indexes
+    split evenly over 2-6 bits, 5 GB of binary16 out) in one call, set up as bench.py sets it
+    up (one device buffer, shard streams back to back, device-side table).  The reference decodes
+    sampled shards -- the first and last of every bitwidth group and a few inside -- bit for bit;
+    over the whole output, every value of a sampled 1 % of positions is a member of its shard's
+    rounded codebook."""
+    from types import SimpleNamespace
+    torch, P, D = gpu
+    ds = S.config1()
+    n = ds.weights_per_shard
+    assert ds.n_shards == 4221 and ds.packed.nbytes == 1073037312
+    packed = torch.from_numpy(ds.packed).cuda()
+    cb_host = np.zeros((ds.n_shards, 64), dtype=np.float32)
+    for s, c in enumerate(ds.codebooks):
+        cb_host[s, :c.size] = c
+    cbs = torch.from_numpy(cb_host).cuda()
+    shards = [SimpleNamespace(bitwidth=int(ds.bitwidths[s]), data=packed[int(ds.offsets[s]):], codebook=cbs[s])
+              for s in range(ds.n_shards)]
+    out = torch.full((ds.n_shards * n,), 7, dtype=torch.float16, device="cuda")
+    ws = torch.empty(max(16, P.sti_decode_workspace_bytes(ds.n_shards)), dtype=torch.uint8, device="cuda")
+    P.sti_decode_shards(P.binding._shard_array(shards), n, out, ws)
+    torch.cuda.synchronize()
+    out = out.view(ds.n_shards, n)
+    sample = set()
+    for k in (2, 3, 4, 5, 6):
+        idx = np.nonzero(ds.bitwidths == k)[0]
+        sample.update([int(idx[0]), int(idx[len(idx) // 3]), int(idx[-1])])
+    for s in sorted(sample):
+        want = oracle_mod.decode_shards([ds.shard(s)], n, oracle_mod.F16)[0]
+        got = out[s].view(torch.int16).cpu().numpy().view(np.uint16)
+        assert np.array_equal(got, want), s
+    # membership over a strided sample of all shards
+    rng = np.random.default_rng(5)
+    cols = torch.from_numpy(np.sort(rng.choice(n, size=n // 100, replace=False))).cuda()
+    sub = out[:, cols].view(torch.int16).cpu().numpy().view(np.uint16)
+    for s in range(0, ds.n_shards, 37):
+        table = oracle_mod.decode_shards(
+            [S.Shard(32, ds.codebooks[s].astype(np.float32), None)], ds.codebooks[s].size, oracle_mod.F16)[0]
+        assert np.isin(sub[s], table).all(), s
