@@ -369,6 +369,18 @@ def test_mfma_many_column_tiles_take_the_band_order(gpu, oracle_mod):
     assert rel_err(got, want) <= TOL["mfma"]
 
 
+@pytest.mark.parametrize("B,L", [(1, 64), (3, 100)])   # few-token route / working-buffer route
+def test_mfma_widest_supported_model(gpu, oracle_mod, B, L):
+    """d_model 2048 (rows of 2048 features in LayerNorm, K = 2048 in the projections, 22-26 column
+    tiles) with 32 shards of which two are absent; weights twice the recipe's scale."""
+    dims = S.Dims(2048, 32, 64, 256, 1e-12)
+    wl = S.small_workload(77, dims, 1, B, L, n_absent=2, io_dtype="f16")
+    S.make_every_term_matter(wl, 21, amp=2.0)
+    want = oracle_mod.model_forward(dims, wl.shards, wl.params, wl.x)
+    got = run_gpu(gpu, wl, "mfma")
+    assert rel_err(got, want) <= TOL["mfma"]
+
+
 def test_mfma_rows_beyond_2gib_of_activations(gpu):
     """350,000 tokens: the FFN activations (T x 3072 binary16) pass 2 GiB, so row addresses need
     64 bits.  Sequences are independent, so the first and the last sequence of the big batch
