@@ -155,7 +155,8 @@ __global__ __launch_bounds__(256) void layernorm_vec_kernel(const float *pre, in
 }
 
 // LayerNorm of rows that already hold sum + bias + residual in binary16 (written by the
-// matrix-core GEMM); d a multiple of 8 and at most 2048; one wave per row.
+// matrix-core GEMM); d a multiple of 8 and at most 2048 (longer rows: the kernel after this
+// one); one wave per row.
 template <int DT>
 __global__ __launch_bounds__(256) void layernorm_f16in_kernel(const _Float16 *pre,
                                                               typename Elem<DT>::type *y,
@@ -214,6 +215,43 @@ __global__ __launch_bounds__(256) void layernorm_f16in_kernel(const _Float16 *pr
                 for (int e = 0; e < 8; ++e) Elem<DT>::store(o + 8 * c + e, t[e]);
             }
         }
+    }
+}
+
+// Same for rows of any length (d a multiple of 8): the row is read three times (mean, variance,
+// output) instead of being kept in registers.
+template <int DT>
+__global__ __launch_bounds__(256) void layernorm_f16in_long_kernel(const _Float16 *pre,
+                                                                   typename Elem<DT>::type *y,
+                                                                   const float *g, const float *b, int T,
+                                                                   int d, float eps)
+{
+    typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+    const int lane = threadIdx.x % 64;
+    const int row = blockIdx.x * 4 + threadIdx.x / 64;
+    if (row >= T) return;
+    const int nchunk = d >> 3;
+    const half8 *r = (const half8 *)(pre + (int64_t)row * d);
+    float s = 0.f;
+    for (int c = lane; c < nchunk; c += 64) {
+        const half8 h = r[c];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) s += (float)h[e];
+    }
+    const float mean = wave_sum(s) / (float)d;
+    float q = 0.f;
+    for (int c = lane; c < nchunk; c += 64) {
+        const half8 h = r[c];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) { const float t = (float)h[e] - mean; q = fmaf(t, t, q); }
+    }
+    const float inv = 1.0f / sqrtf(wave_sum(q) / (float)d + eps);
+    typename Elem<DT>::type *o = y + (int64_t)row * d;
+    for (int c = lane; c < nchunk; c += 64) {
+        const half8 h = r[c];
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+            Elem<DT>::store(o + 8 * c + e, ((float)h[e] - mean) * inv * g[8 * c + e] + b[8 * c + e]);
     }
 }
 
@@ -285,9 +323,17 @@ hipError_t launch_layernorm_f16in(const void *pre_f16, void *y, sti_dtype out_dt
                                   const float *b, int T, int d, float eps, hipStream_t stream)
 {
     if (T <= 0 || d <= 0) return hipSuccess;
-    if (d % 8 || d > 2048) return hipErrorInvalidValue;
+    if (d % 8) return hipErrorInvalidValue;
     dim3 grid((T + 3) / 4);
     const _Float16 *p = (const _Float16 *)pre_f16;
+    if (d > 2048) {
+        switch (out_dtype) {
+            case STI_F32: launch((layernorm_f16in_long_kernel<STI_F32>), grid, dim3(256), 0, stream, p, (float *)y, g, b, T, d, eps); break;
+            case STI_F16: launch((layernorm_f16in_long_kernel<STI_F16>), grid, dim3(256), 0, stream, p, (_Float16 *)y, g, b, T, d, eps); break;
+            case STI_BF16: launch((layernorm_f16in_long_kernel<STI_BF16>), grid, dim3(256), 0, stream, p, (uint16_t *)y, g, b, T, d, eps); break;
+        }
+        return hipGetLastError();
+    }
     switch (out_dtype) {
         case STI_F32: launch((layernorm_f16in_kernel<STI_F32>), grid, dim3(256), 0, stream, p, (float *)y, g, b, T, d, eps); break;
         case STI_F16: launch((layernorm_f16in_kernel<STI_F16>), grid, dim3(256), 0, stream, p, (_Float16 *)y, g, b, T, d, eps); break;

@@ -381,6 +381,19 @@ def test_mfma_widest_supported_model(gpu, oracle_mod, B, L):
     assert rel_err(got, want) <= TOL["mfma"]
 
 
+@pytest.mark.parametrize("d_model", [2112, 4096])
+@pytest.mark.parametrize("B,L", [(1, 40), (3, 100)])   # few-token route / working-buffer route
+def test_mfma_rows_longer_than_2048_features(gpu, oracle_mod, d_model, B, L):
+    """d_model beyond what the row kernels keep in registers (the working-buffer route once
+    failed here, after its first launches, with a HIP error from the LayerNorm launcher)."""
+    dims = S.Dims(d_model, 4, 64, 64, 1e-12)
+    wl = S.small_workload(5, dims, 2, B, L, n_absent=1, io_dtype="f16")
+    S.make_every_term_matter(wl, 8, amp=2.0)
+    want = oracle_mod.model_forward(dims, wl.shards, wl.params, wl.x)
+    got = run_gpu(gpu, wl, "mfma")
+    assert rel_err(got, want) <= TOL["mfma"]
+
+
 def test_mfma_rows_beyond_2gib_of_activations(gpu):
     """350,000 tokens: the FFN activations (T x 3072 binary16) pass 2 GiB, so row addresses need
     64 bits.  Sequences are independent, so the first and the last sequence of the big batch
