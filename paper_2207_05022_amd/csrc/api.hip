@@ -361,7 +361,9 @@ sti_status run_layer(const sti_dims &d, const sti_shard *shards, const sti_layer
     void *qkv = ws + wl.qkv, *ctx = ws + wl.ctx, *h = ws + wl.h, *u = ws + wl.u;
     float *pre = (float *)(ws + wl.pre);
     const sti_dtype act_dtype = f32 ? STI_F32 : STI_F16;
-    const bool skinny = !f32 && few_token_path(d, T);
+    // (a layer with every shard absent has no weights to multiply: at any token count it takes the
+    //  few-token kernels, which then only hand zero sums to the LayerNorms)
+    const bool skinny = !f32 && (few_token_path(d, T) || m == 0);
     const int64_t partial_stride = (int64_t)T * dm;
     int pre_partials = 1;   // partial sums the last K-split GEMM left in `pre`
     auto gemm = [&](const GemmProblem &p, const GemmBlocks &blk) {

@@ -212,6 +212,23 @@ def test_mfma_absent_shards(gpu, oracle_mod, plan):
     assert rel_err(got, want) <= TOL["mfma"]
 
 
+@pytest.mark.parametrize("B,L", [(2, 40), (3, 100), (9, 256)])
+def test_mfma_layers_with_every_shard_absent(gpu, oracle_mod, B, L):
+    """A layer without shards is valid at any token count (the working-buffer route once returned
+    a HIP error for it): alone, and between layers that have shards."""
+    plan = np.array([[4, 0, 32, 3], [0, 0, 0, 0], [2, 6, 0, 5]], dtype=np.int8)
+    wl = S.small_workload(606, MID, 3, B, L, plan=plan, io_dtype="f16")
+    S.make_every_term_matter(wl, 6, amp=4.0)
+    want = oracle_mod.model_forward(MID, wl.shards, wl.params, wl.x)
+    got = run_gpu(gpu, wl, "mfma")
+    assert rel_err(got, want) <= TOL["mfma"]
+    alone = S.small_workload(607, MID, 1, B, L, plan=np.zeros((1, 4), dtype=np.int8), io_dtype="f16")
+    S.make_every_term_matter(alone, 7)
+    want = oracle_mod.layer_forward(MID, alone.shards[0], alone.params[0], alone.x)
+    got = run_gpu(gpu, alone, "mfma", model=False)
+    assert rel_err(got, want) <= TOL["mfma"]
+
+
 @pytest.mark.parametrize("io", ["f32", "f16"])
 def test_mfma_small_model(gpu, oracle_mod, io):
     wl = S.small_workload(19, MID, 4, 2, 65, n_absent=1, io_dtype=io)
