@@ -191,3 +191,20 @@ def test_config1_full_size_sampled_shards(gpu, oracle_mod):
         table = oracle_mod.decode_shards(
             [S.Shard(32, ds.codebooks[s].astype(np.float32), None)], ds.codebooks[s].size, oracle_mod.F16)[0]
         assert np.isin(sub[s], table).all(), s
+
+
+def test_more_than_2_to_the_32_weights_in_one_shard(gpu, oracle_mod):
+    """One 2-bit shard of 2^32 + 24 weights (1 GiB packed, 8.6 GB of binary16 out): positions need
+    64 bits.  Compared block by block so that host copies stay small."""
+    torch, P, D = gpu
+    n = (1 << 32) + 24
+    sh = S.make_shard(np.random.default_rng(320), n, 2)
+    out = torch.full((n,), 7, dtype=torch.float16, device="cuda")
+    P.sti_decode_shards([D.upload_shard(sh)], n, out, None)
+    torch.cuda.synchronize()
+    want = oracle_mod.decode_shards([sh], n, oracle_mod.F16)[0]
+    step = 1 << 28
+    for a in range(0, n, step):
+        b = min(n, a + step)
+        got = out[a:b].view(torch.int16).cpu().numpy().view(np.uint16)
+        assert np.array_equal(got, want[a:b]), a
