@@ -361,9 +361,10 @@ sti_status run_layer(const sti_dims &d, const sti_shard *shards, const sti_layer
     void *qkv = ws + wl.qkv, *ctx = ws + wl.ctx, *h = ws + wl.h, *u = ws + wl.u;
     float *pre = (float *)(ws + wl.pre);
     const sti_dtype act_dtype = f32 ? STI_F32 : STI_F16;
-    // (a layer with every shard absent has no weights to multiply: at any token count it takes the
-    //  few-token kernels, which then only hand zero sums to the LayerNorms)
+    // (a layer with every shard absent has nothing to multiply: on the matrix-core path its two
+    //  LayerNorms run alone, over bias + residual, like those behind the few-token kernels)
     const bool skinny = !f32 && (few_token_path(d, T) || m == 0);
+    const bool no_products = !f32 && m == 0;
     const int64_t partial_stride = (int64_t)T * dm;
     int pre_partials = 1;   // partial sums the last K-split GEMM left in `pre`
     auto gemm = [&](const GemmProblem &p, const GemmBlocks &blk) {
@@ -411,7 +412,8 @@ sti_status run_layer(const sti_dims &d, const sti_shard *shards, const sti_layer
     memset(&p, 0, sizeof(p));
     p.kind = GEMM_OUT; p.T = T; p.n_blocks = m; p.block_rows = dm; p.block_cols = dh; p.d_head = dh;
     p.A = ctx; p.lda = m * dh; p.C = pre; p.ldc = dm; p.bias0 = prm.bo; p.resid = in; p.ldr = dm;
-    STI_TRY(gemm(p, bo));
+    if (no_products) pre_partials = 0;
+    else STI_TRY(gemm(p, bo));
     STI_TRY(layernorm(h, act_dtype, prm.ln1_g, prm.ln1_b, prm.bo, in));
     if (m > 0) {
         memset(&p, 0, sizeof(p));
@@ -423,7 +425,8 @@ sti_status run_layer(const sti_dims &d, const sti_shard *shards, const sti_layer
     p.kind = GEMM_FFN_DOWN; p.T = T; p.n_blocks = m; p.block_rows = dm; p.block_cols = f;
     p.d_head = dh; p.A = u; p.lda = m * f; p.C = pre; p.ldc = dm; p.bias0 = prm.b2; p.resid = h;
     p.ldr = dm;
-    STI_TRY(gemm(p, b2));
+    if (no_products) pre_partials = 0;
+    else STI_TRY(gemm(p, b2));
     STI_TRY(layernorm(out, out_dtype, prm.ln2_g, prm.ln2_b, prm.b2, h));
     return STI_OK;
 }

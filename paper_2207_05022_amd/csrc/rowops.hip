@@ -56,7 +56,7 @@ __global__ __launch_bounds__(256) void layernorm_kernel(const float *pre, int n_
     const float *r = pre + (int64_t)row * d;
     const _Float16 *rs = resid ? resid + (int64_t)row * d : nullptr;
     auto value = [&](int c) {
-        float v = r[c];
+        float v = n_partials > 0 ? r[c] : 0.f;
         for (int s = 1; s < n_partials; ++s) v += r[(int64_t)s * partial_stride + c];
         if (bias) v += bias[c];
         if (rs) v += (float)rs[c];
@@ -112,7 +112,8 @@ __global__ __launch_bounds__(256) void layernorm_vec_kernel(const float *pre, in
         const int c = sub + LPR * j;
         v[j] = f32x4{0.f, 0.f, 0.f, 0.f};
         if (c < nchunk) {
-            f32x4 x = r[c];
+            f32x4 x = {0.f, 0.f, 0.f, 0.f};
+            if (n_partials > 0) x = r[c];
             for (int sp = 1; sp < n_partials; ++sp)
                 x += *(const f32x4 *)(pre + (int64_t)sp * partial_stride + (int64_t)row * d + 4 * c);
             if (bias) x += ((const f32x4 *)bias)[c];
@@ -307,7 +308,7 @@ hipError_t launch_layernorm(const float *pre, int n_partials, int64_t partial_st
                             hipStream_t stream)
 {
     if (T <= 0 || d <= 0) return hipSuccess;
-    if (n_partials < 1) return hipErrorInvalidValue;
+    if (n_partials < 0 || (n_partials > 0 && !pre)) return hipErrorInvalidValue;
     auto al16 = [](const void *p) { return ((uintptr_t)p & 15) == 0; };
     const bool vec = d % 4 == 0 && d <= 2048 && partial_stride % 4 == 0 && al16(pre) && al16(g) && al16(b) && al16(y) &&
                      (!bias || al16(bias)) && (!resid_f16 || al16(resid_f16));

@@ -123,7 +123,7 @@ hipError_t launch_gemm_skinny(const GemmProblem &p, const GemmBlocks &blocks, in
                               int64_t partial_stride, hipStream_t stream);
 
 // rowops.hip
-// v = sum_{s < n_partials} pre[s * partial_stride + t*d + :] + bias[:] + resid[t][:];
+// v = sum_{s < n_partials} pre[s * partial_stride + t*d + :] + bias[:] + resid[t][:]  (n_partials may be 0);
 // y[t][:] = LayerNorm(v) * g + b.  pre float32; bias (float32 [d]) and resid_f16 (binary16
 // [T x d]) may be NULL; y of out_dtype.
 hipError_t launch_layernorm(const float *pre, int n_partials, int64_t partial_stride,
