@@ -283,17 +283,19 @@ __global__ __launch_bounds__(256) void decode_tiled_kernel(Table tab, int total_
 // Outlier dictionary (Section "quantization per shard": the few weights that do not follow
 // the Gaussian are preserved as-is; Section "Implementation": they keep a k-bit placeholder
 // in the index matrix and their original weights and offsets are bookkept).  After the
-// substitution pass the original weights are scattered back.  grid = (chunks, shards).
+// substitution pass the original weights are scattered back.  grid = shards x chunks, flattened
+// (the shard count may pass the limit of the second grid dimension).
 // ---------------------------------------------------------------------------
 namespace {
 
 template <typename Out, typename Table>
-__global__ __launch_bounds__(256) void patch_outliers_kernel(Table table, uint64_t n,
+__global__ __launch_bounds__(256) void patch_outliers_kernel(Table table, uint64_t n, uint32_t chunks,
                                                              typename Out::bits_t *out)
 {
-    const ShardDesc sd = table.get(blockIdx.y);
-    typename Out::bits_t *o = out + (uint64_t)blockIdx.y * n;
-    for (uint32_t t = blockIdx.x * 256 + threadIdx.x; t < sd.n_outliers; t += gridDim.x * 256) {
+    const uint32_t shard = blockIdx.x / chunks, chunk = blockIdx.x - shard * chunks;
+    const ShardDesc sd = table.get(shard);
+    typename Out::bits_t *o = out + (uint64_t)shard * n;
+    for (uint32_t t = chunk * 256 + threadIdx.x; t < sd.n_outliers; t += chunks * 256) {
         const uint32_t pos = sd.outlier_pos[t];
         if (pos < n) o[pos] = Out::cvt(sd.outlier_val[t]);
     }
@@ -305,15 +307,16 @@ hipError_t patch_typed(const ShardDesc *table, const InlineShardTable *inline_ta
 {
     uint32_t chunks = (max_outliers + 255) / 256;
     if (chunks > 1024) chunks = 1024;
-    dim3 grid(chunks, n_shards);
+    while ((uint64_t)chunks * (uint64_t)n_shards > 0x7FFFFFFFull) chunks = (chunks + 1) / 2;
+    dim3 grid(chunks * (uint32_t)n_shards);
     typedef typename Out::bits_t bits_t;
     if (table) {
         TablePtr t{table};
-        patch_outliers_kernel<Out, TablePtr><<<grid, 256, 0, stream>>>(t, n, (bits_t *)out);
+        patch_outliers_kernel<Out, TablePtr><<<grid, 256, 0, stream>>>(t, n, chunks, (bits_t *)out);
     } else {
         TableInline t;
         t.t = *inline_table;
-        patch_outliers_kernel<Out, TableInline><<<grid, 256, 0, stream>>>(t, n, (bits_t *)out);
+        patch_outliers_kernel<Out, TableInline><<<grid, 256, 0, stream>>>(t, n, chunks, (bits_t *)out);
     }
     return hipGetLastError();
 }
@@ -353,7 +356,6 @@ hipError_t launch_patch_outliers(const ShardDesc *table, const InlineShardTable 
                                  sti_dtype out_dtype, hipStream_t stream)
 {
     if (n_shards <= 0 || max_outliers == 0 || n == 0) return hipSuccess;
-    if (n_shards > 65535) return hipErrorInvalidValue;
     switch (out_dtype) {
         case STI_F32: return patch_typed<OutF32>(table, inline_table, n_shards, max_outliers, n, out, stream);
         case STI_F16: return patch_typed<OutF16>(table, inline_table, n_shards, max_outliers, n, out, stream);

@@ -30,7 +30,10 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmProblem p, GemmBlocks
     const bool n_split = (p.kind == GEMM_QKV || p.kind == GEMM_FFN_UP);
     const int N = n_split ? p.n_blocks * p.block_rows : p.block_rows;
     const int K = n_split ? p.block_cols : p.n_blocks * p.block_cols;
-    const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+    // one grid dimension, column tiles fastest (the row-tile count may pass the limit of the others)
+    const int n_tiles = (N + BN - 1) / BN;
+    const int tile_m = blockIdx.x / n_tiles, tile_n = blockIdx.x - tile_m * n_tiles;
+    const int m0 = tile_m * BM, n0 = tile_n * BN;
     const int tid = threadIdx.x;
     const int tx = tid % 16, ty = tid / 16;
     const float *A = (const float *)p.A;
@@ -160,8 +163,9 @@ hipError_t launch_gemm_f32(const GemmProblem &p, const GemmBlocks &blocks, hipSt
     const bool n_split = (p.kind == GEMM_QKV || p.kind == GEMM_FFN_UP);
     const int N = n_split ? p.n_blocks * p.block_rows : p.block_rows;
     if (p.T <= 0 || N <= 0) return hipSuccess;
-    dim3 grid((N + BN - 1) / BN, (p.T + BM - 1) / BM);
-    launch(gemm_f32_kernel, grid, dim3(256), 0, stream, p, blocks);
+    const int64_t tiles = (int64_t)((N + BN - 1) / BN) * ((p.T + BM - 1) / BM);
+    if (tiles > 0x7FFFFFFF) return hipErrorInvalidValue;
+    launch(gemm_f32_kernel, dim3((uint32_t)tiles), dim3(256), 0, stream, p, blocks);
     return hipGetLastError();
 }
 

@@ -208,3 +208,29 @@ def test_more_than_2_to_the_32_weights_in_one_shard(gpu, oracle_mod):
         b = min(n, a + step)
         got = out[a:b].view(torch.int16).cpu().numpy().view(np.uint16)
         assert np.array_equal(got, want[a:b]), a
+
+
+def test_more_shards_than_a_grid_dimension_with_dictionaries(gpu, oracle_mod):
+    """70,000 small shards, each with an outlier dictionary: the shard count passes the limit of
+    a grid's second and third dimension (the scatter pass once refused such a call after the
+    substitution pass had already run)."""
+    from types import SimpleNamespace
+    torch, P, D = gpu
+    n_shards, n, k, n_out = 70000, 64, 4, 2
+    rng = np.random.default_rng(70000)
+    packed = rng.integers(0, 256, size=(n_shards, n * k // 8), dtype=np.uint8)
+    codebooks = np.sort(rng.normal(0, 0.02, size=(n_shards, 1 << k)).astype(np.float32), axis=1)
+    pos = np.sort(np.stack([rng.choice(n, size=n_out, replace=False) for _ in range(n_shards)]), axis=1).astype(np.uint32)
+    val = rng.normal(0, 0.3, size=(n_shards, n_out)).astype(np.float32)
+    host = [S.Shard(k, packed[s], codebooks[s], pos[s], val[s]) for s in range(n_shards)]
+    want = oracle_mod.decode_shards(host, n, oracle_mod.F16)
+    dp, dc = torch.from_numpy(packed).cuda(), torch.from_numpy(codebooks).cuda()
+    dpos, dval = torch.from_numpy(pos.view(np.int32)).cuda(), torch.from_numpy(val).cuda()
+    dev = [SimpleNamespace(bitwidth=k, data=dp[s], codebook=dc[s], outlier_pos=dpos[s], outlier_val=dval[s])
+           for s in range(n_shards)]
+    out = torch.full((n_shards * n,), 7, dtype=torch.float16, device="cuda")
+    ws = torch.empty(P.sti_decode_workspace_bytes(n_shards), dtype=torch.uint8, device="cuda")
+    P.sti_decode_shards(dev, n, out, ws)
+    torch.cuda.synchronize()
+    got = out.view(torch.int16).cpu().numpy().view(np.uint16).reshape(n_shards, n)
+    assert np.array_equal(got, want)
