@@ -532,3 +532,56 @@ def test_mfma_random_shapes(gpu, oracle_mod):
         want = oracle_mod.model_forward(dims, wl.shards, wl.params, wl.x)
         got = run_gpu(gpu, wl, "mfma")
         assert rel_err(got, want) <= TOL["mfma"], (case, d, M, f, B, L, n_abs, n_layers)
+
+
+def test_concurrent_calls_from_host_threads(gpu):
+    """Four host threads, each with a stream and a workspace of its own, run model forwards of
+    both routes (and decode calls that upload a shard table) at the same time: every result is
+    bit for bit the single-threaded one.  (The library's only shared state is the pinned ring
+    that table uploads go through.)"""
+    import threading
+    torch, P, D = gpu
+    prec = P.STI_PREC_F16_MFMA
+    prepared = []
+    for seed, (B, L) in enumerate([(2, 60), (5, 128), (1, 100), (9, 256)]):
+        wl = S.small_workload(8800 + seed, WIDE if seed == 3 else MID, 3, B, L, n_absent=1, io_dtype="f16")
+        shards, params, x = D.upload_workload(wl)
+        store = P.make_store(D.store_from_plan(shards))
+        ws = torch.empty(P.sti_model_workspace_bytes(wl.dims, 3, B, L, prec), dtype=torch.uint8, device="cuda")
+        ref = torch.empty_like(x)
+        P.sti_model_forward(wl.dims, store, params, wl.plan, x, ref, prec, ws)
+        prepared.append((wl, store, params, x, ref, shards))
+    n = 4096
+    host = [S.make_shard(np.random.default_rng(s), n, int(k))
+            for s, k in enumerate(np.random.default_rng(0).choice([2, 3, 4, 5, 6], size=100))]
+    dev = [D.upload_shard(s) for s in host]
+    dref = torch.empty(len(dev) * n, dtype=torch.float16, device="cuda")
+    dws = torch.empty(P.sti_decode_workspace_bytes(len(dev)), dtype=torch.uint8, device="cuda")
+    P.sti_decode_shards(dev, n, dref, dws)
+    torch.cuda.synchronize()
+    bad = []
+
+    def worker(i):
+        wl, store, params, x, ref, _ = prepared[i]
+        B, L = int(x.shape[0]), int(x.shape[1])
+        stream = torch.cuda.Stream()
+        with torch.cuda.stream(stream):
+            ws = torch.empty(P.sti_model_workspace_bytes(wl.dims, 3, B, L, prec), dtype=torch.uint8, device="cuda")
+            y = torch.empty_like(x)
+            out, ows = torch.empty_like(dref), torch.empty_like(dws)
+            for it in range(30):
+                y.fill_(float("nan"))
+                P.sti_model_forward(wl.dims, store, params, wl.plan, x, y, prec, ws)
+                P.sti_decode_shards(dev, n, out, ows)
+                if it % 10 == 9:
+                    stream.synchronize()
+                    if not torch.equal(y, ref) or not torch.equal(out.view(torch.int16), dref.view(torch.int16)):
+                        bad.append((i, it))
+        stream.synchronize()
+
+    threads = [threading.Thread(target=worker, args=(i,)) for i in range(4)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not bad, bad
