@@ -159,3 +159,18 @@ def test_quantizer_random_layers_and_distributions():
             w = rng.normal(0, 1e-6, (M, wsh))
         w = np.asarray(w, dtype=np.float32)
         check_against_reference(dims, w, k, run_gpu(dims, w, k, max_out=4096))
+
+
+def test_quantizer_reports_a_layer_without_inliers():
+    """The outlier rule is an absolute log likelihood (below -4): with a standard deviation above
+    e^4 / sqrt(2 pi) = 21.8 even the mean is an outlier.  The call then reports status 1, counts
+    every weight as an outlier and fills the dictionaries, in offset order, as far as they have
+    room (the reference quantizer refuses such a layer)."""
+    w = np.random.default_rng(1).normal(0, 100.0, (4, MID.weights_per_shard)).astype(np.float32)
+    g = run_gpu(MID, w, 4, max_out=512)
+    assert g["stats"].status == 1 and g["stats"].n_outliers == w.size
+    assert np.array_equal(g["cnt"].cpu().numpy(), np.full(4, MID.weights_per_shard))
+    assert abs(g["stats"].mean - float(np.mean(w.astype(np.float64)))) <= 1e-12 * 100
+    for s in range(4):
+        assert np.array_equal(g["pos"][s].cpu().numpy(), np.arange(512))
+        assert np.array_equal(g["val"][s].cpu().numpy().view(np.uint32), w[s, :512].view(np.uint32))
