@@ -304,6 +304,39 @@ def test_mfma_rejects_unsupported_dims(gpu):
     assert ei.value.status == 2
 
 
+@pytest.mark.parametrize("prec", ["f32", "mfma"])
+@pytest.mark.parametrize("B,L", [(2, 40), (5, 128)])
+def test_rejected_calls_report_their_status_and_write_nothing(gpu, prec, B, L):
+    """Every argument is checked before the first launch: a call that is rejected because of its last
+    layer's plan, its workspace or its buffers leaves the output as it was."""
+    torch, P, D = gpu
+    precision = P.STI_PREC_F32 if prec == "f32" else P.STI_PREC_F16_MFMA
+    wl = S.small_workload(1, MID, 4, B, L, n_absent=1, io_dtype="f16")
+    shards, params, x = D.upload_workload(wl)
+    store = P.make_store(D.store_from_plan(shards))
+    ws = torch.empty(P.sti_model_workspace_bytes(MID, 4, B, L, precision), dtype=torch.uint8, device="cuda")
+
+    def rejected(status, plan=wl.plan, xin=x, workspace=ws):
+        y = torch.full_like(x, float("nan"))
+        with pytest.raises(P.StiError) as ei:
+            P.sti_model_forward(MID, store, params, plan, xin, y, precision, workspace)
+        torch.cuda.synchronize()
+        assert ei.value.status == status
+        assert bool(torch.isnan(y.float()).all())
+
+    present = int(np.argwhere(wl.plan[3] != 0)[0][0])
+    plan = wl.plan.copy()
+    plan[3, present] = [k for k in (2, 3, 4, 5, 6, 32) if k != wl.plan[3, present]][0]
+    rejected(4, plan=plan)                                   # a version the store does not hold
+    plan = wl.plan.copy()
+    plan[3, present] = 7
+    rejected(3, plan=plan)                                   # not a bitwidth
+    one_layer = P.sti_workspace_bytes(MID, B, L, precision)  # least the model call can work in
+    rejected(6, workspace=ws[:one_layer - 1])                # workspace too small
+    shifted = torch.empty(x.numel() + 8, dtype=x.dtype, device="cuda")[1:1 + x.numel()].view_as(x)
+    rejected(5, xin=shifted)                                 # input not 16-byte aligned
+
+
 # ------------------------------------------------------------------ outlier dictionary
 
 def _with_outliers(wl, seed, fraction=0.0015):

@@ -291,3 +291,38 @@ def test_pipeline_random_models_buffers_and_slots(gpu):
         y4, _ = rig.run()
         assert torch.equal(y3, ref) and torch.equal(y4, ref), case
         rig.pipe.close()
+
+
+@pytest.mark.parametrize("prec", ["f32", "mfma"])
+def test_pipeline_rejected_calls_write_nothing_and_keep_the_preload_buffer(gpu, prec):
+    """A call rejected for its last layer's plan or for its workspace leaves the output and the
+    pipeline's resident shards as they were: the next good call still hits them all."""
+    torch, P, D = gpu
+    wl = S.small_workload(77, MID, 4, 2, 60, n_absent=1)
+    total = sum(plan_bytes(MID, wl.plan))
+    rig = Rig(gpu, wl, prec, preload_bytes=total // 2)
+    ref = rig.reference()
+    n_res, b_res = expected_resident(MID, wl.plan, total // 2)
+    y, _ = rig.run()
+    assert torch.equal(y, ref)
+
+    def rejected(status, plan=wl.plan, workspace=rig.ws):
+        y = torch.full_like(rig.x, float("nan"))
+        with pytest.raises(P.StiError) as ei:
+            rig.pipe.forward(rig.host_store, rig.params, plan, rig.x, y, rig.precision, workspace)
+        torch.cuda.synchronize()
+        assert ei.value.status == status
+        assert bool(torch.isnan(y.float()).all())
+
+    present = int(np.argwhere(wl.plan[3] != 0)[0][0])
+    plan = wl.plan.copy()
+    plan[3, present] = [k for k in (2, 3, 4, 5, 6, 32) if k != wl.plan[3, present]][0]
+    rejected(4, plan=plan)                                   # a version the store does not hold
+    plan = wl.plan.copy()
+    plan[3, present] = 7
+    rejected(3, plan=plan)                                   # not a bitwidth
+    rejected(6, workspace=rig.ws[:rig.ws.numel() // 2])      # workspace too small
+    y, st = rig.run()
+    assert torch.equal(y, ref)
+    assert st["shards_hit"] == n_res and st["bytes_copied"] == total - b_res
+    rig.pipe.close()
