@@ -52,6 +52,14 @@ def lib():
         L.oracle_model_forward.argtypes = [
             C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_double, C.c_int32, C.POINTER(_Shard),
             C.POINTER(_Params), C.c_void_p, C.c_void_p, C.c_int32, C.c_int32]
+        L.oracle_layer_forward_masked.restype = C.c_int
+        L.oracle_layer_forward_masked.argtypes = [
+            C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_double, C.POINTER(_Shard),
+            C.POINTER(_Params), C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]
+        L.oracle_model_forward_masked.restype = C.c_int
+        L.oracle_model_forward_masked.argtypes = [
+            C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_double, C.c_int32, C.POINTER(_Shard),
+            C.POINTER(_Params), C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]
         _lib = L
     return _lib
 
@@ -132,8 +140,16 @@ def decode_shards(shards: Sequence, n_weights: int, dtype: int = F32) -> np.ndar
     return out
 
 
-def layer_forward(dims, shards: Sequence, params, x: np.ndarray, taps: bool = False):
-    """One layer over the present shards; x [B, L, d] (any float dtype, widened exactly)."""
+def _lengths(key_lengths, B: int) -> np.ndarray:
+    lens = np.ascontiguousarray(key_lengths, dtype=np.int32)
+    if lens.shape != (B,):
+        raise ValueError("need one key length per sequence")
+    return lens
+
+
+def layer_forward(dims, shards: Sequence, params, x: np.ndarray, taps: bool = False, key_lengths=None):
+    """One layer over the present shards; x [B, L, d] (any float dtype, widened exactly).
+    key_lengths [B] (optional): real positions per padded sequence; the rest get no attention."""
     keep: list = []
     arr = _shard_array(shards, keep)
     if len(shards) != dims.n_heads:
@@ -147,6 +163,15 @@ def layer_forward(dims, shards: Sequence, params, x: np.ndarray, taps: bool = Fa
     attn = np.empty_like(x64) if taps else None
     h = np.empty_like(x64) if taps else None
     ffn = np.empty_like(x64) if taps else None
+    if key_lengths is not None:
+        if taps:
+            raise ValueError("taps are not offered with key lengths")
+        lens = _lengths(key_lengths, B)
+        rc = lib().oracle_layer_forward_masked(
+            dims.d_model, dims.n_heads, dims.d_head, dims.ffn_per_shard, float(dims.ln_eps), arr,
+            C.byref(p), x64.ctypes.data, y.ctypes.data, B, L, lens.ctypes.data)
+        _check(rc, "layer_forward_masked")
+        return y
     rc = lib().oracle_layer_forward_taps(
         dims.d_model, dims.n_heads, dims.d_head, dims.ffn_per_shard, float(dims.ln_eps), arr,
         C.byref(p), x64.ctypes.data, y.ctypes.data, B, L,
@@ -158,8 +183,9 @@ def layer_forward(dims, shards: Sequence, params, x: np.ndarray, taps: bool = Fa
     return y
 
 
-def model_forward(dims, shards: Sequence[Sequence], params: Sequence, x: np.ndarray) -> np.ndarray:
-    """shards [n_layers][M] (None = absent), params [n_layers]."""
+def model_forward(dims, shards: Sequence[Sequence], params: Sequence, x: np.ndarray,
+                  key_lengths=None) -> np.ndarray:
+    """shards [n_layers][M] (None = absent), params [n_layers]; key_lengths as in layer_forward."""
     keep: list = []
     n_layers = len(shards)
     flat = [s for row in shards for s in row]
@@ -172,6 +198,13 @@ def model_forward(dims, shards: Sequence[Sequence], params: Sequence, x: np.ndar
     x64 = np.ascontiguousarray(x, dtype=np.float64)
     B, L, d = x64.shape
     y = np.empty_like(x64)
+    if key_lengths is not None:
+        lens = _lengths(key_lengths, B)
+        rc = lib().oracle_model_forward_masked(
+            dims.d_model, dims.n_heads, dims.d_head, dims.ffn_per_shard, float(dims.ln_eps), n_layers,
+            arr, ps, x64.ctypes.data, y.ctypes.data, B, L, lens.ctypes.data)
+        _check(rc, "model_forward_masked")
+        return y
     rc = lib().oracle_model_forward(
         dims.d_model, dims.n_heads, dims.d_head, dims.ffn_per_shard, float(dims.ln_eps), n_layers,
         arr, ps, x64.ctypes.data, y.ctypes.data, B, L)

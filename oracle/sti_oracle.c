@@ -240,30 +240,31 @@ static void layer_norm_rows(double *y, const double *v, int64_t T, int64_t d, co
 static double gelu_erf(double z) { return z * 0.5 * (1.0 + erf(z / sqrt(2.0))); }
 
 /* Attention of one head over one sequence: C = softmax(Q K^T / sqrt(dh)) V.
- * q, k, v, c are [L][dh] with row stride ld. */
+ * q, k, v, c are [L][dh] with row stride ld.  Only the first Lk keys take part (Lk = L for a
+ * sequence without padding): a padded position gets no attention weight from any query. */
 static void attention_head(double *c, const double *q, const double *k, const double *v, int64_t L,
-                           int64_t dh, int64_t ld, double *score_rows /* [L][L] scratch */)
+                           int64_t Lk, int64_t dh, int64_t ld, double *score_rows /* [L][L] scratch */)
 {
     double scale = 1.0 / sqrt((double)dh);
 #pragma omp parallel for schedule(static)
     for (int64_t i = 0; i < L; ++i) {
         double *s = score_rows + i * L;
         double mx = -INFINITY;
-        for (int64_t j = 0; j < L; ++j) {
+        for (int64_t j = 0; j < Lk; ++j) {
             double acc = 0.0;
             for (int64_t e = 0; e < dh; ++e) acc += q[i * ld + e] * k[j * ld + e];
             s[j] = acc * scale;
             if (s[j] > mx) mx = s[j];
         }
         double den = 0.0;
-        for (int64_t j = 0; j < L; ++j) {
+        for (int64_t j = 0; j < Lk; ++j) {
             s[j] = exp(s[j] - mx);
             den += s[j];
         }
-        for (int64_t j = 0; j < L; ++j) s[j] /= den;
+        for (int64_t j = 0; j < Lk; ++j) s[j] /= den;
         for (int64_t e = 0; e < dh; ++e) {
             double acc = 0.0;
-            for (int64_t j = 0; j < L; ++j) acc += s[j] * v[j * ld + e];
+            for (int64_t j = 0; j < Lk; ++j) acc += s[j] * v[j * ld + e];
             c[i * ld + e] = acc;
         }
     }
@@ -275,13 +276,17 @@ static void attention_head(double *c, const double *q, const double *k, const do
  *   attn_out = b_o + sum_i C_i Wo_i^T          (before residual and LayerNorm)
  *   h_out    = LayerNorm1(x + attn)
  *   ffn_out  = b_2 + sum_i U_i W2_i^T          (before residual and LayerNorm) */
-int oracle_layer_forward_taps(int32_t d, int32_t M, int32_t dh, int32_t f, double eps,
+static int layer_forward_impl(int32_t d, int32_t M, int32_t dh, int32_t f, double eps,
                               const oracle_shard *shards, const oracle_layer_params *p,
-                              const double *x, double *y, int32_t B, int32_t L, double *attn_out,
+                              const double *x, double *y, int32_t B, int32_t L,
+                              const int32_t *key_lengths /* [B] or NULL */, double *attn_out,
                               double *h_out, double *ffn_out)
 {
     if (!shards || !p || !x || !y) return ORACLE_ERR_ARG;
     if (d <= 0 || M <= 0 || dh <= 0 || f <= 0 || B < 0 || L < 0) return ORACLE_ERR_ARG;
+    if (key_lengths)
+        for (int32_t b = 0; b < B; ++b)
+            if (key_lengths[b] < 1 || key_lengths[b] > L) return ORACLE_ERR_ARG;
     for (int i = 0; i < M; ++i) {
         int k = shards[i].bitwidth;
         if (k == 0) continue;
@@ -323,8 +328,8 @@ int oracle_layer_forward_taps(int32_t d, int32_t M, int32_t dh, int32_t f, doubl
         linear_rows(kk, dh, x, d, T, w + off_k, dh, d, p->bk + (int64_t)i * dh);
         linear_rows(v, dh, x, d, T, w + off_v, dh, d, p->bv + (int64_t)i * dh);
         for (int64_t b = 0; b < B; ++b)
-            attention_head(c + b * L * dh, q + b * L * dh, kk + b * L * dh, v + b * L * dh, L, dh,
-                           dh, sc);
+            attention_head(c + b * L * dh, q + b * L * dh, kk + b * L * dh, v + b * L * dh, L,
+                           key_lengths ? key_lengths[b] : L, dh, dh, sc);
         linear_rows_accumulate(attn, d, c, dh, T, w + off_o, d, dh);
     }
     if (attn_out) memcpy(attn_out, attn, (size_t)T * d * sizeof(double));
@@ -354,17 +359,39 @@ done:
     return rc;
 }
 
+int oracle_layer_forward_taps(int32_t d, int32_t M, int32_t dh, int32_t f, double eps,
+                              const oracle_shard *shards, const oracle_layer_params *p,
+                              const double *x, double *y, int32_t B, int32_t L, double *attn_out,
+                              double *h_out, double *ffn_out)
+{
+    return layer_forward_impl(d, M, dh, f, eps, shards, p, x, y, B, L, NULL, attn_out, h_out, ffn_out);
+}
+
 int oracle_layer_forward(int32_t d, int32_t M, int32_t dh, int32_t f, double eps,
                          const oracle_shard *shards, const oracle_layer_params *p, const double *x,
                          double *y, int32_t B, int32_t L)
 {
-    return oracle_layer_forward_taps(d, M, dh, f, eps, shards, p, x, y, B, L, NULL, NULL, NULL);
+    return layer_forward_impl(d, M, dh, f, eps, shards, p, x, y, B, L, NULL, NULL, NULL, NULL);
+}
+
+/* Inputs padded to a common length (Section "Prerequisite: Offline Profiling": the length is
+ * fixed after padding): sequence b holds key_lengths[b] real positions, 1 <= key_lengths[b] <= L,
+ * followed by padding.  Padded positions are computed like any other row but no query attends
+ * to them. */
+int oracle_layer_forward_masked(int32_t d, int32_t M, int32_t dh, int32_t f, double eps,
+                                const oracle_shard *shards, const oracle_layer_params *p,
+                                const double *x, double *y, int32_t B, int32_t L,
+                                const int32_t *key_lengths)
+{
+    if (!key_lengths) return ORACLE_ERR_ARG;
+    return layer_forward_impl(d, M, dh, f, eps, shards, p, x, y, B, L, key_lengths, NULL, NULL, NULL);
 }
 
 /* Layers 0 .. n_layers-1 in order; shards is [n_layers][M], params [n_layers]. */
-int oracle_model_forward(int32_t d, int32_t M, int32_t dh, int32_t f, double eps, int32_t n_layers,
-                         const oracle_shard *shards, const oracle_layer_params *params,
-                         const double *x, double *y, int32_t B, int32_t L)
+static int model_forward_impl(int32_t d, int32_t M, int32_t dh, int32_t f, double eps, int32_t n_layers,
+                              const oracle_shard *shards, const oracle_layer_params *params,
+                              const double *x, double *y, int32_t B, int32_t L,
+                              const int32_t *key_lengths)
 {
     if (n_layers < 0 || !x || !y) return ORACLE_ERR_ARG;
     size_t n = (size_t)B * L * d;
@@ -374,10 +401,28 @@ int oracle_model_forward(int32_t d, int32_t M, int32_t dh, int32_t f, double eps
     memcpy(cur, x, n * sizeof(double));
     int rc = ORACLE_OK;
     for (int l = 0; l < n_layers && rc == ORACLE_OK; ++l) {
-        rc = oracle_layer_forward(d, M, dh, f, eps, shards + (size_t)l * M, &params[l], cur, nxt, B, L);
+        rc = layer_forward_impl(d, M, dh, f, eps, shards + (size_t)l * M, &params[l], cur, nxt, B, L,
+                                key_lengths, NULL, NULL, NULL);
         double *t = cur; cur = nxt; nxt = t;
     }
     if (rc == ORACLE_OK) memcpy(y, cur, n * sizeof(double));
     free(cur); free(nxt);
     return rc;
+}
+
+int oracle_model_forward(int32_t d, int32_t M, int32_t dh, int32_t f, double eps, int32_t n_layers,
+                         const oracle_shard *shards, const oracle_layer_params *params,
+                         const double *x, double *y, int32_t B, int32_t L)
+{
+    return model_forward_impl(d, M, dh, f, eps, n_layers, shards, params, x, y, B, L, NULL);
+}
+
+/* The same key lengths in every layer. */
+int oracle_model_forward_masked(int32_t d, int32_t M, int32_t dh, int32_t f, double eps,
+                                int32_t n_layers, const oracle_shard *shards,
+                                const oracle_layer_params *params, const double *x, double *y,
+                                int32_t B, int32_t L, const int32_t *key_lengths)
+{
+    if (!key_lengths) return ORACLE_ERR_ARG;
+    return model_forward_impl(d, M, dh, f, eps, n_layers, shards, params, x, y, B, L, key_lengths);
 }

@@ -52,8 +52,9 @@ def shard32_from_blocks(blocks) -> S.Shard:
     return S.Shard(32, flat, None)
 
 
-def dense_torch_layer(dims: S.Dims, shards, params: S.LayerParams, x: np.ndarray) -> np.ndarray:
-    """Full layer as a stock dense post-LN encoder layer in float64."""
+def dense_torch_layer(dims: S.Dims, shards, params: S.LayerParams, x: np.ndarray,
+                      key_lengths=None) -> np.ndarray:
+    """Full layer as a stock dense post-LN encoder layer in float64 (key_lengths: padding mask)."""
     import torch
     d, M, dh, f = dims.d_model, dims.n_heads, dims.d_head, dims.ffn_per_shard
     blocks = [split_blocks(dims, np_decode(s, dims.weights_per_shard).astype(np.float64))
@@ -80,7 +81,10 @@ def dense_torch_layer(dims: S.Dims, shards, params: S.LayerParams, x: np.ndarray
         layer.norm2.weight.copy_(t(params.ln2_g)); layer.norm2.bias.copy_(t(params.ln2_b))
         # the python path (no fused fast path) so that eps and ordering are the stock ones
         torch.backends.mha.set_fastpath_enabled(False)
-        y = layer(t(x))
+        pad = None
+        if key_lengths is not None:
+            pad = torch.arange(x.shape[1])[None, :] >= torch.as_tensor(np.asarray(key_lengths))[:, None]
+        y = layer(t(x), src_key_padding_mask=pad)
     return y.numpy()
 
 
@@ -348,3 +352,61 @@ def test_planted_mistakes_show_only_when_every_term_matters(oracle_mod):
     strong = effects(wl)
     for name, e in strong.items():
         assert e > 3 * TOL16, (name, e)
+
+
+# ---------------------------------------------------------------- padded sequences
+
+def _padded_case(seed, B=4, L=19):
+    rng = np.random.default_rng(seed)
+    shards = [S.make_shard(rng, SMALL.weights_per_shard, k) for k in (4, 32, 6)]
+    params = random_params(rng, SMALL)
+    x = rng.normal(0, 1, (B, L, SMALL.d_model))
+    lens = np.array([L, 1, 7, L - 1][:B], dtype=np.int32)
+    return shards, params, x, lens
+
+
+def test_padding_mask_matches_the_stock_layer(oracle_mod):
+    """Keys beyond a sequence's length get no attention weight: torch's key-padding mask
+    (float64, dense matrices assembled above) gives the same rows, padded ones included."""
+    shards, params, x, lens = _padded_case(21)
+    for s in shards:                                  # weights large enough for attention to matter
+        if s.bitwidth == 32:
+            s.data = (np.asarray(s.data) * 8).astype(np.float32)
+        else:
+            s.codebook = (s.codebook * 8).astype(np.float32)
+    got = oracle_mod.layer_forward(SMALL, shards, params, x, key_lengths=lens)
+    want = dense_torch_layer(SMALL, shards, params, x, key_lengths=lens)
+    unmasked = dense_torch_layer(SMALL, shards, params, x)
+    assert np.max(np.abs(got - want)) < 1e-10
+    assert np.max(np.abs(unmasked - want)) > 1e-2     # the mask changes the result at this scale
+
+
+def test_padded_rows_do_not_reach_real_rows(oracle_mod):
+    """The real positions of a padded sequence come out as if the sequence had been run alone at
+    its own length, whatever the padding holds; full lengths reproduce the unmasked layer bit for
+    bit."""
+    shards, params, x, lens = _padded_case(22)
+    rows = [[s for s in shards], [shards[0], None, shards[2]]]
+    prm = [params, random_params(np.random.default_rng(5), SMALL)]
+    got = oracle_mod.model_forward(SMALL, rows, prm, x, key_lengths=lens)
+    for b, n in enumerate(lens):
+        alone = oracle_mod.model_forward(SMALL, rows, prm, x[b:b + 1, :n])
+        assert np.max(np.abs(got[b, :n] - alone[0])) < 1e-12
+    x2 = x.copy()
+    for b, n in enumerate(lens):
+        x2[b, n:] = 1e3 * np.random.default_rng(b).normal(size=x2[b, n:].shape)
+    again = oracle_mod.model_forward(SMALL, rows, prm, x2, key_lengths=lens)
+    for b, n in enumerate(lens):
+        assert np.array_equal(again[b, :n], got[b, :n])
+    full = np.full(len(lens), x.shape[1], dtype=np.int32)
+    assert np.array_equal(oracle_mod.model_forward(SMALL, rows, prm, x, key_lengths=full),
+                          oracle_mod.model_forward(SMALL, rows, prm, x))
+
+
+def test_key_lengths_outside_the_sequence_are_refused(oracle_mod):
+    shards, params, x, lens = _padded_case(23)
+    for bad in (0, x.shape[1] + 1, -3):
+        lens2 = lens.copy()
+        lens2[2] = bad
+        with pytest.raises(Exception):
+            oracle_mod.layer_forward(SMALL, shards, params, x, key_lengths=lens2)
