@@ -188,6 +188,36 @@ sti_status sti_model_forward(const sti_dims *dims, int n_layers, const sti_shard
                              sti_precision precision, void *workspace, size_t workspace_bytes,
                              void *hip_stream);
 
+/* ---------------------------------------------------------------------------
+ * Padded sequences.  The paper runs inputs padded to one fixed length (Section
+ * "Prerequisite: Offline Profiling": the input length is fixed after padding, e.g. 128;
+ * Section "Compute Planning").  With the variants below, sequence b holds key_lengths[b]
+ * real positions followed by padding, and in every layer
+ *
+ *   C_i = softmax over the first key_lengths[b] keys only ( Q_i K_i^T / sqrt(dh) ) V_i,
+ *
+ * i.e. no query gives attention weight to a padded position.  The rows of padded
+ * positions are computed like any other (from the real keys) and written to y; the real
+ * rows do not depend on what the padding holds, as long as it is finite.
+ *
+ *  key_lengths  DEVICE int32 [batch], 4-byte aligned, read by the kernels when they run
+ *               (it must stay unchanged until then).  Values are clamped to 1 .. seq.
+ *               NULL is STI_ERR_NULL unless batch * seq == 0.
+ * All other arguments, the workspace sizes and the error behaviour are those of the
+ * entry point without the suffix, which is the case key_lengths[b] == seq for all b.
+ * ------------------------------------------------------------------------- */
+sti_status sti_layer_forward_masked(const sti_dims *dims, const sti_shard *shards,
+                                    const sti_layer_params *params, const void *x, void *y,
+                                    sti_dtype io_dtype, int batch, int seq, const int32_t *key_lengths,
+                                    sti_precision precision, void *workspace, size_t workspace_bytes,
+                                    void *hip_stream);
+
+sti_status sti_model_forward_masked(const sti_dims *dims, int n_layers, const sti_shard *store,
+                                    const sti_layer_params *params, const int8_t *plan, const void *x,
+                                    void *y, sti_dtype io_dtype, int batch, int seq,
+                                    const int32_t *key_lengths, sti_precision precision, void *workspace,
+                                    size_t workspace_bytes, void *hip_stream);
+
 /* Workspace size with which sti_model_forward decompresses several layers per launch
  * (Section "Submodel execution" keeps one layer's working buffer because memory is scarce on
  * the paper's devices; with room for one buffer per layer, a few layers are decompressed by
@@ -251,6 +281,14 @@ sti_status sti_pipeline_forward(sti_pipeline *pipeline, int n_layers, const sti_
                                 void *y, sti_dtype io_dtype, int batch, int seq,
                                 sti_precision precision, void *workspace, size_t workspace_bytes,
                                 void *hip_stream, sti_pipeline_stats *stats);
+
+/* sti_pipeline_forward over padded sequences: key_lengths as for sti_model_forward_masked. */
+sti_status sti_pipeline_forward_masked(sti_pipeline *pipeline, int n_layers, const sti_shard *store,
+                                       const sti_layer_params *params, const int8_t *plan, const void *x,
+                                       void *y, sti_dtype io_dtype, int batch, int seq,
+                                       const int32_t *key_lengths, sti_precision precision,
+                                       void *workspace, size_t workspace_bytes, void *hip_stream,
+                                       sti_pipeline_stats *stats);
 
 /* Waits for the handle's copies, then releases its stream and events (not the buffers). */
 sti_status sti_pipeline_destroy(sti_pipeline *pipeline);

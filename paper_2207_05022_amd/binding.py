@@ -83,6 +83,15 @@ def _load():
         L.sti_layer_forward.argtypes = [
             C.POINTER(StiDims), C.POINTER(StiShard), C.POINTER(StiLayerParams), C.c_void_p,
             C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.sti_layer_forward_masked.restype = C.c_int
+        L.sti_layer_forward_masked.argtypes = [
+            C.POINTER(StiDims), C.POINTER(StiShard), C.POINTER(StiLayerParams), C.c_void_p,
+            C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_int, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.sti_model_forward_masked.restype = C.c_int
+        L.sti_model_forward_masked.argtypes = [
+            C.POINTER(StiDims), C.c_int, C.POINTER(StiShard), C.POINTER(StiLayerParams),
+            C.POINTER(C.c_int8), C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_int,
+            C.c_void_p, C.c_size_t, C.c_void_p]
         L.sti_model_forward.restype = C.c_int
         L.sti_model_forward.argtypes = [
             C.POINTER(StiDims), C.c_int, C.POINTER(StiShard), C.POINTER(StiLayerParams),
@@ -106,6 +115,11 @@ def _load():
     L.sti_pipeline_create.restype = C.c_int
     L.sti_pipeline_create.argtypes = [C.POINTER(StiDims), C.c_void_p, C.c_size_t, C.c_void_p,
                                       C.c_size_t, C.POINTER(C.c_void_p)]
+    L.sti_pipeline_forward_masked.restype = C.c_int
+    L.sti_pipeline_forward_masked.argtypes = [
+        C.c_void_p, C.c_int, C.POINTER(StiShard), C.POINTER(StiLayerParams), C.POINTER(C.c_int8),
+        C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_int, C.c_void_p, C.c_size_t,
+        C.c_void_p, C.POINTER(StiPipelineStats)]
     L.sti_pipeline_forward.restype = C.c_int
     L.sti_pipeline_forward.argtypes = [
         C.c_void_p, C.c_int, C.POINTER(StiShard), C.POINTER(StiLayerParams), C.POINTER(C.c_int8),
@@ -206,6 +220,16 @@ def sti_model_workspace_bytes(dims, n_layers: int, batch: int, seq: int, precisi
     return int(lib.sti_model_workspace_bytes(C.byref(d), int(n_layers), int(batch), int(seq), int(precision)))
 
 
+def _key_lengths_ptr(key_lengths, batch: int):
+    """key_lengths: CUDA int32 tensor [batch] (None passes a null pointer through)."""
+    if key_lengths is None:
+        return None
+    import torch
+    if key_lengths.dtype != torch.int32 or tuple(key_lengths.shape) != (batch,):
+        raise ValueError("key_lengths must be an int32 tensor with one entry per sequence")
+    return _ptr(key_lengths)
+
+
 def sti_layer_forward(dims, shards: Sequence, params, x, y, precision: int, workspace,
                       stream=None) -> None:
     """x, y: CUDA tensors [batch, seq, d_model] of one dtype; shards: M entries, None = absent."""
@@ -219,6 +243,21 @@ def sti_layer_forward(dims, shards: Sequence, params, x, y, precision: int, work
                                _stream_handle(stream))
     if st != 0:
         raise StiError(st, "sti_layer_forward")
+
+
+def sti_layer_forward_masked(dims, shards: Sequence, params, x, y, key_lengths, precision: int,
+                             workspace, stream=None) -> None:
+    """As sti_layer_forward; key_lengths: CUDA int32 tensor [batch], real positions per sequence."""
+    d = make_dims(dims)
+    arr = _shard_array(shards)
+    p = make_params(params)
+    batch, seq = int(x.shape[0]), int(x.shape[1])
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    st = lib.sti_layer_forward_masked(C.byref(d), arr, C.byref(p), _ptr(x), _ptr(y), _dtype_code(x),
+                                      batch, seq, _key_lengths_ptr(key_lengths, batch), int(precision),
+                                      _ptr(workspace), ws_bytes, _stream_handle(stream))
+    if st != 0:
+        raise StiError(st, "sti_layer_forward_masked")
 
 
 def make_store(store_rows: Sequence[Sequence[dict]]) -> "C.Array":
@@ -260,6 +299,28 @@ def sti_model_forward(dims, store, params: Sequence, plan, x, y, precision: int,
         raise StiError(st, "sti_model_forward")
 
 
+def sti_model_forward_masked(dims, store, params: Sequence, plan, x, y, key_lengths, precision: int,
+                             workspace, stream=None) -> None:
+    """As sti_model_forward; key_lengths: CUDA int32 tensor [batch], the same in every layer."""
+    import numpy as np
+    d = make_dims(dims)
+    plan = np.ascontiguousarray(plan, dtype=np.int8)
+    n_layers = int(plan.shape[0]) if plan.ndim == 2 else 0
+    if not isinstance(store, C.Array):
+        store = make_store(store)
+    ps = (StiLayerParams * max(1, n_layers))()
+    for l in range(n_layers):
+        ps[l] = make_params(params[l])
+    batch, seq = int(x.shape[0]), int(x.shape[1])
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    st = lib.sti_model_forward_masked(C.byref(d), n_layers, store, ps,
+                                      plan.ctypes.data_as(C.POINTER(C.c_int8)), _ptr(x), _ptr(y),
+                                      _dtype_code(x), batch, seq, _key_lengths_ptr(key_lengths, batch),
+                                      int(precision), _ptr(workspace), ws_bytes, _stream_handle(stream))
+    if st != 0:
+        raise StiError(st, "sti_model_forward_masked")
+
+
 def sti_profile_begin() -> None:
     st = lib.sti_profile_begin()
     if st != 0:
@@ -295,8 +356,10 @@ class StiPipeline:
             raise StiError(st, "sti_pipeline_create")
         self._h = handle
 
-    def forward(self, store, params: Sequence, plan, x, y, precision: int, workspace, stream=None) -> dict:
-        """store: make_store(...) of versions whose ``data`` are pinned host tensors."""
+    def forward(self, store, params: Sequence, plan, x, y, precision: int, workspace, stream=None,
+                key_lengths=None) -> dict:
+        """store: make_store(...) of versions whose ``data`` are pinned host tensors.
+        With key_lengths (CUDA int32 tensor [batch]) the call goes to sti_pipeline_forward_masked."""
         import numpy as np
         plan = np.ascontiguousarray(plan, dtype=np.int8)
         n_layers = int(plan.shape[0]) if plan.ndim == 2 else 0
@@ -307,6 +370,15 @@ class StiPipeline:
             ps[l] = make_params(params[l])
         stats = StiPipelineStats()
         ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+        if key_lengths is not None:
+            st = lib.sti_pipeline_forward_masked(
+                self._h, n_layers, store, ps, plan.ctypes.data_as(C.POINTER(C.c_int8)), _ptr(x), _ptr(y),
+                _dtype_code(x), int(x.shape[0]), int(x.shape[1]),
+                _key_lengths_ptr(key_lengths, int(x.shape[0])), int(precision), _ptr(workspace), ws_bytes,
+                _stream_handle(stream), C.byref(stats))
+            if st != 0:
+                raise StiError(st, "sti_pipeline_forward_masked")
+            return {n: int(getattr(stats, n)) for n, _ in StiPipelineStats._fields_}
         st = lib.sti_pipeline_forward(self._h, n_layers, store, ps,
                                       plan.ctypes.data_as(C.POINTER(C.c_int8)), _ptr(x), _ptr(y),
                                       _dtype_code(x), int(x.shape[0]), int(x.shape[1]), int(precision),

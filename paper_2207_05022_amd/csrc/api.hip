@@ -291,7 +291,7 @@ static_assert(kSkinnyMaxTokens >= 192, "the partial-sum planes are sized with kS
 sti_status run_layer(const sti_dims &d, const sti_shard *shards, const sti_layer_params &prm,
                      const void *in, void *out, sti_dtype out_dtype, int B, int Lseq,
                      sti_precision prec, uint8_t *ws, const WorkspaceLayout &wl, hipStream_t stream,
-                     const void *predecoded)
+                     const void *predecoded, const int32_t *key_lengths)
 {
     const int dm = d.d_model, M = d.n_heads, dh = d.d_head, f = d.ffn_per_shard;
     const int T = B * Lseq;
@@ -405,8 +405,8 @@ sti_status run_layer(const sti_dims &d, const sti_shard *shards, const sti_layer
         p.bias0 = prm.bq; p.bias1 = prm.bk; p.bias2 = prm.bv;
         STI_TRY(gemm(p, bq));
         STI_TRY(timed(STI_K_ATTENTION, stream, [&] {
-            return f32 ? launch_attention_f32((const float *)qkv, (float *)ctx, B, Lseq, m, dh, stream)
-                       : launch_attention_mfma(qkv, ctx, B, Lseq, m, dh, stream);
+            return f32 ? launch_attention_f32((const float *)qkv, (float *)ctx, B, Lseq, m, dh, key_lengths, stream)
+                       : launch_attention_mfma(qkv, ctx, B, Lseq, m, dh, key_lengths, stream);
         }));
     }
     memset(&p, 0, sizeof(p));
@@ -443,9 +443,64 @@ sti_status check_io(const void *x, void *y, sti_dtype io, int64_t T, int d)
     return STI_OK;
 }
 
+sti_status check_key_lengths(const int32_t *key_lengths)
+{
+    if (!key_lengths) return STI_ERR_NULL;
+    return aligned(key_lengths, 4) ? STI_OK : STI_ERR_ALIGN;
+}
+
 }  // namespace sti
 
 using namespace sti;
+
+namespace {
+
+// masked: the call came through a *_masked entry point and key_lengths must be usable
+sti_status layer_forward(const sti_dims *dims, const sti_shard *shards,
+                         const sti_layer_params *params, const void *x, void *y,
+                         sti_dtype io_dtype, int batch, int seq, bool masked, const int32_t *key_lengths,
+                         sti_precision precision, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    sti_status st = check_dims(dims, batch, seq, precision);
+    if (st != STI_OK) return st;
+    if (!shards) return STI_ERR_NULL;
+    st = check_params(params);
+    if (st != STI_OK) return st;
+    const int64_t T = (int64_t)batch * seq;
+    st = check_io(x, y, io_dtype, T, dims->d_model);
+    if (st != STI_OK) return st;
+    if (masked && T > 0) {
+        st = check_key_lengths(key_lengths);
+        if (st != STI_OK) return st;
+    }
+    for (int i = 0; i < dims->n_heads; ++i) {
+        st = check_layer_shard(shards[i]);
+        if (st != STI_OK) return st;
+    }
+    const WorkspaceLayout wl = workspace_layout(*dims, T, precision);
+    if (!workspace || workspace_bytes < wl.total) return STI_ERR_WORKSPACE;
+    if (!aligned(workspace, 256)) return STI_ERR_ALIGN;
+    if (T == 0) return STI_OK;
+
+    hipStream_t stream = (hipStream_t)hip_stream;
+    uint8_t *ws = (uint8_t *)workspace;
+    const sti_dtype act = (precision == STI_PREC_F32) ? STI_F32 : STI_F16;
+    const void *in = x;
+    if (io_dtype != act) {
+        STI_TRY(timed(STI_K_CONVERT, stream, [&] { return launch_convert(x, io_dtype, ws + wl.act[0], act, (uint64_t)T * dims->d_model, stream); }));
+        in = ws + wl.act[0];
+    }
+    return run_layer(*dims, shards, *params, in, y, io_dtype, batch, seq, precision, ws, wl, stream,
+                     nullptr, masked ? key_lengths : nullptr);
+}
+
+sti_status model_forward(const sti_dims *dims, int n_layers, const sti_shard *store,
+                         const sti_layer_params *params, const int8_t *plan, const void *x,
+                         void *y, sti_dtype io_dtype, int batch, int seq, bool masked,
+                         const int32_t *key_lengths, sti_precision precision, void *workspace,
+                         size_t workspace_bytes, void *hip_stream);
+
+}  // namespace
 
 extern "C" {
 
@@ -548,32 +603,18 @@ sti_status sti_layer_forward(const sti_dims *dims, const sti_shard *shards,
                              sti_dtype io_dtype, int batch, int seq, sti_precision precision,
                              void *workspace, size_t workspace_bytes, void *hip_stream)
 {
-    sti_status st = check_dims(dims, batch, seq, precision);
-    if (st != STI_OK) return st;
-    if (!shards) return STI_ERR_NULL;
-    st = check_params(params);
-    if (st != STI_OK) return st;
-    const int64_t T = (int64_t)batch * seq;
-    st = check_io(x, y, io_dtype, T, dims->d_model);
-    if (st != STI_OK) return st;
-    for (int i = 0; i < dims->n_heads; ++i) {
-        st = check_layer_shard(shards[i]);
-        if (st != STI_OK) return st;
-    }
-    const WorkspaceLayout wl = workspace_layout(*dims, T, precision);
-    if (!workspace || workspace_bytes < wl.total) return STI_ERR_WORKSPACE;
-    if (!aligned(workspace, 256)) return STI_ERR_ALIGN;
-    if (T == 0) return STI_OK;
+    return layer_forward(dims, shards, params, x, y, io_dtype, batch, seq, false, nullptr, precision,
+                         workspace, workspace_bytes, hip_stream);
+}
 
-    hipStream_t stream = (hipStream_t)hip_stream;
-    uint8_t *ws = (uint8_t *)workspace;
-    const sti_dtype act = (precision == STI_PREC_F32) ? STI_F32 : STI_F16;
-    const void *in = x;
-    if (io_dtype != act) {
-        STI_TRY(timed(STI_K_CONVERT, stream, [&] { return launch_convert(x, io_dtype, ws + wl.act[0], act, (uint64_t)T * dims->d_model, stream); }));
-        in = ws + wl.act[0];
-    }
-    return run_layer(*dims, shards, *params, in, y, io_dtype, batch, seq, precision, ws, wl, stream);
+sti_status sti_layer_forward_masked(const sti_dims *dims, const sti_shard *shards,
+                                    const sti_layer_params *params, const void *x, void *y,
+                                    sti_dtype io_dtype, int batch, int seq, const int32_t *key_lengths,
+                                    sti_precision precision, void *workspace, size_t workspace_bytes,
+                                    void *hip_stream)
+{
+    return layer_forward(dims, shards, params, x, y, io_dtype, batch, seq, true, key_lengths, precision,
+                         workspace, workspace_bytes, hip_stream);
 }
 
 sti_status sti_model_forward(const sti_dims *dims, int n_layers, const sti_shard *store,
@@ -582,12 +623,40 @@ sti_status sti_model_forward(const sti_dims *dims, int n_layers, const sti_shard
                              sti_precision precision, void *workspace, size_t workspace_bytes,
                              void *hip_stream)
 {
+    return model_forward(dims, n_layers, store, params, plan, x, y, io_dtype, batch, seq, false, nullptr,
+                         precision, workspace, workspace_bytes, hip_stream);
+}
+
+sti_status sti_model_forward_masked(const sti_dims *dims, int n_layers, const sti_shard *store,
+                                    const sti_layer_params *params, const int8_t *plan, const void *x,
+                                    void *y, sti_dtype io_dtype, int batch, int seq,
+                                    const int32_t *key_lengths, sti_precision precision, void *workspace,
+                                    size_t workspace_bytes, void *hip_stream)
+{
+    return model_forward(dims, n_layers, store, params, plan, x, y, io_dtype, batch, seq, true, key_lengths,
+                         precision, workspace, workspace_bytes, hip_stream);
+}
+
+}  // extern "C"
+
+namespace {
+
+sti_status model_forward(const sti_dims *dims, int n_layers, const sti_shard *store,
+                         const sti_layer_params *params, const int8_t *plan, const void *x,
+                         void *y, sti_dtype io_dtype, int batch, int seq, bool masked,
+                         const int32_t *key_lengths, sti_precision precision, void *workspace,
+                         size_t workspace_bytes, void *hip_stream)
+{
     sti_status st = check_dims(dims, batch, seq, precision);
     if (st != STI_OK) return st;
     if (n_layers < 0) return STI_ERR_DIMS;
     const int64_t T = (int64_t)batch * seq;
     st = check_io(x, y, io_dtype, T, dims->d_model);
     if (st != STI_OK) return st;
+    if (masked && T > 0) {
+        st = check_key_lengths(key_lengths);
+        if (st != STI_OK) return st;
+    }
     const int M = dims->n_heads;
     if (n_layers > 0 && (!store || !params || !plan)) return STI_ERR_NULL;
     std::vector<sti_shard> chosen;
@@ -705,13 +774,17 @@ sti_status sti_model_forward(const sti_dims *dims, int n_layers, const sti_shard
         }
         const void *predecoded = whole_model_fits ? (const void *)(ws + wl.w16 + first_shard[l] * wsh * 2) : nullptr;
         st = run_layer(*dims, &chosen[(size_t)l * M], params[l], cur, out, last ? io_dtype : act,
-                       batch, seq, precision, ws, wl, stream, predecoded);
+                       batch, seq, precision, ws, wl, stream, predecoded, masked ? key_lengths : nullptr);
         if (st != STI_OK) return st;
         cur = out;
         next_buf ^= 1;
     }
     return STI_OK;
 }
+
+}  // namespace
+
+extern "C" {
 
 size_t sti_model_workspace_bytes(const sti_dims *dims, int n_layers, int batch, int seq, sti_precision precision)
 {

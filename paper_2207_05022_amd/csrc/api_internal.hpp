@@ -32,8 +32,10 @@ sti_status check_io(const void *x, void *y, sti_dtype io, int64_t T, int d);
 sti_status run_layer(const sti_dims &d, const sti_shard *shards, const sti_layer_params &prm,
                      const void *in, void *out, sti_dtype out_dtype, int B, int Lseq,
                      sti_precision prec, uint8_t *ws, const WorkspaceLayout &wl, hipStream_t stream,
-                     const void *predecoded = nullptr);
+                     const void *predecoded = nullptr, const int32_t *key_lengths = nullptr);
 // `predecoded`: the layer's present shards already sit there in fragment-tiled binary16 order
 // (outliers applied); run_layer then decompresses nothing.
+// `key_lengths` (device, [B]): real positions per padded sequence; null = every position is real.
+sti_status check_key_lengths(const int32_t *key_lengths);   // non-null, 4-byte aligned
 
 }  // namespace sti

@@ -11,6 +11,10 @@
 // The maximum and the sum of a query's row are per lane; lanes l and l^32 own the two
 // halves of a query's keys and exchange their maxima (once per key block with the running
 // maximum of the online softmax, once in all when the sequence is short, see SHORT).
+//
+// Padded sequences (the input length is fixed after padding, Section "Prerequisite: Offline
+// Profiling"): with key_lengths, sequence b attends to its first key_lengths[b] positions only
+// (clamped to 1..L); rows of padded positions are still computed, from those keys.
 #include "sti_internal.hpp"
 
 namespace sti {
@@ -32,7 +36,8 @@ __device__ inline int vt_stride(int Lp) { return Lp + 8; }
 // known before the first exponential, and the output accumulators are never rescaled.
 template <int NW, int SHORT>
 __global__ __launch_bounds__(NW * 64, 2) void attention_mfma_kernel(const _Float16 *qkv, _Float16 *ctx,
-                                                                 int L, int Lp, int m)
+                                                                 int L, int Lp, int m,
+                                                                 const int32_t *key_lengths)
 {
     constexpr int QB = NW * 32;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
@@ -44,6 +49,8 @@ __global__ __launch_bounds__(NW * 64, 2) void attention_mfma_kernel(const _Float
     const int b = blockIdx.z, p = blockIdx.y;
     const int64_t ld = (int64_t)m * 3 * DH;
     const _Float16 *base = qkv + (int64_t)b * L * ld + (int64_t)p * 3 * DH;
+    int Lk = L;   // keys that take part
+    if (key_lengths) Lk = min(max(key_lengths[b], 1), L);
 
     // this lane's query row as the B operand of S^T = K Q^T (asked for first: the loads below
     // and these share one round trip to memory)
@@ -56,7 +63,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attention_mfma_kernel(const _Float
         qf[s] = __builtin_bit_cast(half8, v);
     }
 
-    // Stage K (row-major; rows >= L are zero) and V transposed, 128 keys per pass: all loads
+    // Stage K (row-major; rows >= Lk are zero) and V transposed, 128 keys per pass: all loads
     // of a pass are issued before the first LDS store, so a pass costs one round trip.
     //   K: a thread takes 16 bytes of rows tid/8 + 8 NW j;
     //   V: a lane takes two consecutive keys and 8 features, so that the 64 lanes of one LDS
@@ -71,7 +78,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attention_mfma_kernel(const _Float
         for (int j = 0; j < KJ; ++j) {
             const int r = r0p + (tid >> 3) + NW * 8 * j;
             kreg[j] = u32x4{0, 0, 0, 0};
-            if (r < L) kreg[j] = *(const u32x4 *)(base + (int64_t)r * ld + DH + kc);
+            if (r < Lk) kreg[j] = *(const u32x4 *)(base + (int64_t)r * ld + DH + kc);
         }
 #pragma unroll
         for (int j = 0; j < VJ; ++j) {
@@ -80,8 +87,8 @@ __global__ __launch_bounds__(NW * 64, 2) void attention_mfma_kernel(const _Float
             const int r0 = 2 * pair;
             v0[j] = u32x4{0, 0, 0, 0};
             v1[j] = u32x4{0, 0, 0, 0};
-            if (item < v_items && r0 < L) v0[j] = *(const u32x4 *)(base + (int64_t)r0 * ld + 2 * DH + c);
-            if (item < v_items && r0 + 1 < L) v1[j] = *(const u32x4 *)(base + (int64_t)(r0 + 1) * ld + 2 * DH + c);
+            if (item < v_items && r0 < Lk) v0[j] = *(const u32x4 *)(base + (int64_t)r0 * ld + 2 * DH + c);
+            if (item < v_items && r0 + 1 < Lk) v1[j] = *(const u32x4 *)(base + (int64_t)(r0 + 1) * ld + 2 * DH + c);
         }
 #pragma unroll
         for (int j = 0; j < KJ; ++j) {
@@ -114,7 +121,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attention_mfma_kernel(const _Float
 #pragma unroll
         for (int v = 0; v < 16; ++v) o[e][v] = 0.f;
 
-    const int nkb = Lp / 32;
+    const int nkb = (Lk + 31) / 32;   // key blocks beyond the last real key are skipped
     // O^T += V^T P^T over the two k16 steps of key block kb; pk = the block's probabilities
     auto add_pv = [&](int kb, const uint32_t (&pk)[8]) {
 #pragma unroll
@@ -146,11 +153,11 @@ __global__ __launch_bounds__(NW * 64, 2) void attention_mfma_kernel(const _Float
                 half8 kf = *(const half8 *)(Ks + (size_t)(kb * 32 + lr) * KPAD + s * 16 + g * 8);
                 sc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf, qf[s], sc[kb], 0, 0, 0);
             }
-            if (kb * 32 + 32 > L) {   // keys past L sit in the last block only
+            if (kb * 32 + 32 > Lk) {   // keys past Lk sit in the last block only
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     const int key = kb * 32 + (v >> 2) * 8 + g * 4 + (v & 3);
-                    sc[kb][v] = (key < L) ? sc[kb][v] : -INFINITY;
+                    sc[kb][v] = (key < Lk) ? sc[kb][v] : -INFINITY;
                 }
             }
 #pragma unroll
@@ -188,7 +195,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attention_mfma_kernel(const _Float
         for (int v = 0; v < 16; ++v) {
             const int key = kb * 32 + (v >> 2) * 8 + g * 4 + (v & 3);
             float x = s_acc[v] * scale;
-            x = (key < L) ? x : -INFINITY;
+            x = (key < Lk) ? x : -INFINITY;
             s_acc[v] = x;
             bmax = fmaxf(bmax, x);
         }
@@ -231,7 +238,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attention_mfma_kernel(const _Float
 }  // namespace
 
 hipError_t launch_attention_mfma(const void *qkv, void *ctx, int B, int L, int m, int dh,
-                                 hipStream_t stream)
+                                 const int32_t *key_lengths, hipStream_t stream)
 {
     if (B <= 0 || L <= 0 || m <= 0) return hipSuccess;
     if (dh != DH) return hipErrorInvalidValue;
@@ -253,24 +260,24 @@ hipError_t launch_attention_mfma(const void *qkv, void *ctx, int B, int L, int m
         dim3 grid((L + 63) / 64, m, B);
         if (Lp <= 128)
             launch((attention_mfma_kernel<2, 4>), grid, dim3(128), lds, stream, (const _Float16 *)qkv,
-                                                                          (_Float16 *)ctx, L, Lp, m);
+                                                                          (_Float16 *)ctx, L, Lp, m, key_lengths);
         else if (Lp <= 256)
             launch((attention_mfma_kernel<2, 8>), grid, dim3(128), lds, stream, (const _Float16 *)qkv,
-                                                                          (_Float16 *)ctx, L, Lp, m);
+                                                                          (_Float16 *)ctx, L, Lp, m, key_lengths);
         else
             launch((attention_mfma_kernel<2, 0>), grid, dim3(128), lds, stream, (const _Float16 *)qkv,
-                                                                          (_Float16 *)ctx, L, Lp, m);
+                                                                          (_Float16 *)ctx, L, Lp, m, key_lengths);
     } else {
         dim3 grid((L + 127) / 128, m, B);
         if (Lp <= 128)
             launch((attention_mfma_kernel<4, 4>), grid, dim3(256), lds, stream, (const _Float16 *)qkv,
-                                                                          (_Float16 *)ctx, L, Lp, m);
+                                                                          (_Float16 *)ctx, L, Lp, m, key_lengths);
         else if (Lp <= 256)
             launch((attention_mfma_kernel<4, 8>), grid, dim3(256), lds, stream, (const _Float16 *)qkv,
-                                                                          (_Float16 *)ctx, L, Lp, m);
+                                                                          (_Float16 *)ctx, L, Lp, m, key_lengths);
         else
             launch((attention_mfma_kernel<4, 0>), grid, dim3(256), lds, stream, (const _Float16 *)qkv,
-                                                                          (_Float16 *)ctx, L, Lp, m);
+                                                                          (_Float16 *)ctx, L, Lp, m, key_lengths);
     }
     return hipGetLastError();
 }

@@ -112,9 +112,10 @@ __device__ inline float wave_sum(float v)
 }
 
 // One wave per query row: scores over all keys, wavefront-reduction softmax,
-// then the context row.  Dynamic LDS: 4 waves x (L + dh) floats.
+// then the context row.  Dynamic LDS: 4 waves x (L + dh) floats.  With key_lengths, sequence b
+// attends to its first key_lengths[b] positions only (clamped to 1..L).
 __global__ __launch_bounds__(256) void attention_f32_kernel(const float *qkv, float *ctx, int L,
-                                                            int m, int dh)
+                                                            int m, int dh, const int32_t *key_lengths)
 {
     extern __shared__ float smem[];
     const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
@@ -123,6 +124,8 @@ __global__ __launch_bounds__(256) void attention_f32_kernel(const float *qkv, fl
     const int b = blockIdx.z, p = blockIdx.y;
     const int i = blockIdx.x * 4 + wave;
     if (i >= L) return;  // whole wave leaves; no workgroup barrier below
+    int Lk = L;
+    if (key_lengths) Lk = min(max(key_lengths[b], 1), L);
     const int64_t ld = (int64_t)m * 3 * dh;
     const float *base = qkv + (int64_t)b * L * ld + (int64_t)p * 3 * dh;
     const float *q = base + (int64_t)i * ld;
@@ -130,7 +133,7 @@ __global__ __launch_bounds__(256) void attention_f32_kernel(const float *qkv, fl
     __builtin_amdgcn_wave_barrier();
     const float scale = 1.0f / sqrtf((float)dh);
     float mx = -INFINITY;
-    for (int j = lane; j < L; j += 64) {
+    for (int j = lane; j < Lk; j += 64) {
         const float *k = base + (int64_t)j * ld + dh;
         float s = 0.f;
         for (int e = 0; e < dh; ++e) s = fmaf(qrow[e], k[e], s);
@@ -140,7 +143,7 @@ __global__ __launch_bounds__(256) void attention_f32_kernel(const float *qkv, fl
     }
     mx = wave_max(mx);
     float den = 0.f;
-    for (int j = lane; j < L; j += 64) {
+    for (int j = lane; j < Lk; j += 64) {
         float e = expf(prob[j] - mx);
         prob[j] = e;
         den += e;
@@ -151,7 +154,7 @@ __global__ __launch_bounds__(256) void attention_f32_kernel(const float *qkv, fl
     float *out = ctx + ((int64_t)b * L + i) * ((int64_t)m * dh) + (int64_t)p * dh;
     for (int e = lane; e < dh; e += 64) {
         float acc = 0.f;
-        for (int j = 0; j < L; ++j) acc = fmaf(prob[j], base[(int64_t)j * ld + 2 * dh + e], acc);
+        for (int j = 0; j < Lk; ++j) acc = fmaf(prob[j], base[(int64_t)j * ld + 2 * dh + e], acc);
         out[e] = acc * inv;
     }
 }
@@ -170,12 +173,12 @@ hipError_t launch_gemm_f32(const GemmProblem &p, const GemmBlocks &blocks, hipSt
 }
 
 hipError_t launch_attention_f32(const float *qkv, float *ctx, int B, int L, int m, int dh,
-                                hipStream_t stream)
+                                const int32_t *key_lengths, hipStream_t stream)
 {
     if (B <= 0 || L <= 0 || m <= 0) return hipSuccess;
     dim3 grid((L + 3) / 4, m, B);
     size_t lds = (size_t)4 * (L + dh) * sizeof(float);
-    launch(attention_f32_kernel, grid, dim3(256), lds, stream, qkv, ctx, L, m, dh);
+    launch(attention_f32_kernel, grid, dim3(256), lds, stream, qkv, ctx, L, m, dh, key_lengths);
     return hipGetLastError();
 }
 

@@ -197,11 +197,16 @@ sti_status sti_pipeline_destroy(sti_pipeline *p)
     return st;
 }
 
-sti_status sti_pipeline_forward(sti_pipeline *pl, int n_layers, const sti_shard *store,
-                                const sti_layer_params *params, const int8_t *plan, const void *x,
-                                void *y, sti_dtype io_dtype, int batch, int seq,
-                                sti_precision precision, void *workspace, size_t workspace_bytes,
-                                void *hip_stream, sti_pipeline_stats *stats)
+}  // extern "C"
+
+namespace {
+
+// masked: the call came through sti_pipeline_forward_masked and key_lengths must be usable
+sti_status pipeline_forward(sti_pipeline *pl, int n_layers, const sti_shard *store,
+                            const sti_layer_params *params, const int8_t *plan, const void *x,
+                            void *y, sti_dtype io_dtype, int batch, int seq, bool masked,
+                            const int32_t *key_lengths, sti_precision precision, void *workspace,
+                            size_t workspace_bytes, void *hip_stream, sti_pipeline_stats *stats)
 {
     if (!pl) return STI_ERR_NULL;
     if (stats) memset(stats, 0, sizeof(*stats));
@@ -212,6 +217,10 @@ sti_status sti_pipeline_forward(sti_pipeline *pl, int n_layers, const sti_shard 
     const int64_t T = (int64_t)batch * seq;
     st = check_io(x, y, io_dtype, T, dims->d_model);
     if (st != STI_OK) return st;
+    if (masked && T > 0) {
+        st = check_key_lengths(key_lengths);
+        if (st != STI_OK) return st;
+    }
     const int M = dims->n_heads;
     if (n_layers > 0 && (!store || !params || !plan)) return STI_ERR_NULL;
     std::vector<sti_shard> chosen;
@@ -343,7 +352,7 @@ sti_status sti_pipeline_forward(sti_pipeline *pl, int n_layers, const sti_shard 
         const bool last = (l == n_layers - 1);
         void *out = last ? y : (void *)(ws + wl.act[next_buf]);
         st = run_layer(*dims, row, params[l], cur, out, last ? io_dtype : act, batch, seq, precision,
-                       ws, wl, stream);
+                       ws, wl, stream, nullptr, masked ? key_lengths : nullptr);
         if (st != STI_OK) return st;
         if (slot_off > 0) {
             STI_TRY(hipEventRecord(pl->computed[slot], stream));
@@ -356,6 +365,31 @@ sti_status sti_pipeline_forward(sti_pipeline *pl, int n_layers, const sti_shard 
     pl->has_last = true;
     pl->resident.swap(want);
     return STI_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+sti_status sti_pipeline_forward(sti_pipeline *pl, int n_layers, const sti_shard *store,
+                                const sti_layer_params *params, const int8_t *plan, const void *x,
+                                void *y, sti_dtype io_dtype, int batch, int seq,
+                                sti_precision precision, void *workspace, size_t workspace_bytes,
+                                void *hip_stream, sti_pipeline_stats *stats)
+{
+    return pipeline_forward(pl, n_layers, store, params, plan, x, y, io_dtype, batch, seq, false, nullptr,
+                            precision, workspace, workspace_bytes, hip_stream, stats);
+}
+
+sti_status sti_pipeline_forward_masked(sti_pipeline *pl, int n_layers, const sti_shard *store,
+                                       const sti_layer_params *params, const int8_t *plan, const void *x,
+                                       void *y, sti_dtype io_dtype, int batch, int seq,
+                                       const int32_t *key_lengths, sti_precision precision,
+                                       void *workspace, size_t workspace_bytes, void *hip_stream,
+                                       sti_pipeline_stats *stats)
+{
+    return pipeline_forward(pl, n_layers, store, params, plan, x, y, io_dtype, batch, seq, true, key_lengths,
+                            precision, workspace, workspace_bytes, hip_stream, stats);
 }
 
 }  // extern "C"

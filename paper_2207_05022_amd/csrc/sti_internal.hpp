@@ -95,9 +95,10 @@ struct GemmProblem {
 
 // float32 path (layer_f32.hip): A, C, resid are float32; weights are float32 blocks.
 hipError_t launch_gemm_f32(const GemmProblem &p, const GemmBlocks &blocks, hipStream_t stream);
-// qkv [T x m*3*dh] float32 (per shard: q, k, v each dh wide) -> ctx [T x m*dh] float32
+// qkv [T x m*3*dh] float32 (per shard: q, k, v each dh wide) -> ctx [T x m*dh] float32.
+// key_lengths (device, [B], may be null): keys of sequence b beyond key_lengths[b] take no part.
 hipError_t launch_attention_f32(const float *qkv, float *ctx, int B, int L, int m, int dh,
-                                hipStream_t stream);
+                                const int32_t *key_lengths, hipStream_t stream);
 
 // binary16 MFMA path (gemm_wide.hip, attention_mfma.hip): A and C are binary16.  QKV / FFN_UP
 // apply bias (and GELU); OUT / FFN_DOWN add bias[N] and the binary16 residual, leaving the
@@ -111,7 +112,7 @@ bool gemm_wide_supported(const GemmProblem &p, const GemmBlocks &blocks);
 int gemm_wide_k_splits(const GemmProblem &p);
 int gemm_wide_max_k_splits(int64_t T, int N);
 hipError_t launch_attention_mfma(const void *qkv, void *ctx, int B, int L, int m, int dh,
-                                 hipStream_t stream);
+                                 const int32_t *key_lengths, hipStream_t stream);
 
 // Few-token variant of the MFMA GEMM (gemm_skinny.hip): T <= kSkinnyMaxTokens, split-K inside the
 // workgroup and, for the K-split kinds, across `k_splits` workgroups that write float32

@@ -137,6 +137,22 @@ def test_layer_argument_errors(P):
     assert layer(P, batch=0) == 0                   # empty batch: nothing to do
 
 
+def test_masked_layer_argument_errors(P):
+    d = P.binding.make_dims(Dims(d=64, M=2, dh=64, f=64))
+    arr = (P.StiShard * 2)(shard(P, 4), shard(P, 0, None, None))
+    prm = P.StiLayerParams(*([FAKE] * 10))
+
+    def call(lengths, batch=1, x=FAKE):
+        return P.lib.sti_layer_forward_masked(C.byref(d), arr, C.byref(prm), x, FAKE + 0x100000, 0, batch, 8,
+                                              lengths, 0, None, 0, None)
+
+    assert call(None) == 1                          # key lengths are required ...
+    assert call(None, batch=0) == 6                 # ... unless there are no tokens (then: workspace)
+    assert call(FAKE + 2) == 5                      # 4-byte alignment
+    assert call(FAKE + 4) == 6                      # accepted; the missing workspace is next
+    assert call(FAKE + 4, x=None) == 1              # the checks of the plain entry point still apply
+
+
 def test_model_argument_errors(P):
     d = P.binding.make_dims(Dims(d=64, M=2, dh=64, f=64))
     store = (P.StiShard * 12)(*[shard(P, k) for k in (2, 3, 4, 5, 6, 32)] * 2)

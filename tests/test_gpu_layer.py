@@ -618,3 +618,87 @@ def test_concurrent_calls_from_host_threads(gpu):
     for t in threads:
         t.join()
     assert not bad, bad
+
+
+# ------------------------------------------------------------------ padded sequences
+
+def _key_lengths(L, B, seed):
+    """Lengths that hit the edges (1, L, around multiples of 32) and random ones."""
+    rng = np.random.default_rng(seed)
+    edges = [L, 1, min(L, 32), min(L, 33), max(1, L - 1), min(L, 64), min(L, 31)]
+    lens = [edges[b] if b < len(edges) else int(rng.integers(1, L + 1)) for b in range(B)]
+    return np.asarray(lens, dtype=np.int32)
+
+
+def _run_masked(gpu, wl, prec, lens, route):
+    torch, P, D = gpu
+    precision = P.STI_PREC_F32 if prec == "f32" else P.STI_PREC_F16_MFMA
+    shards, params, xd = D.upload_workload(wl)
+    ld = None if lens is None else torch.from_numpy(lens).cuda()
+    y = torch.full_like(xd, float("nan"))
+    B, L = int(xd.shape[0]), int(xd.shape[1])
+    store = P.make_store(D.store_from_plan(shards))
+    if route == "whole":      # room for every layer's working buffer
+        ws = torch.empty(P.sti_model_workspace_bytes(wl.dims, wl.n_layers, B, L, precision), dtype=torch.uint8, device="cuda")
+    else:
+        ws = torch.empty(P.sti_workspace_bytes(wl.dims, B, L, precision), dtype=torch.uint8, device="cuda")
+    if route == "layer":
+        assert wl.n_layers == 1
+        if ld is None:
+            P.sti_layer_forward(wl.dims, shards[0], params[0], xd, y, precision, ws)
+        else:
+            P.sti_layer_forward_masked(wl.dims, shards[0], params[0], xd, y, ld, precision, ws)
+    elif ld is None:
+        P.sti_model_forward(wl.dims, store, params, wl.plan, xd, y, precision, ws)
+    else:
+        P.sti_model_forward_masked(wl.dims, store, params, wl.plan, xd, y, ld, precision, ws)
+    torch.cuda.synchronize()
+    return y
+
+
+@pytest.mark.parametrize("prec,dims,B,L,route", [
+    ("f32", SMALL, 5, 19, "layer"), ("f32", MID, 8, 70, "model"),
+    ("mfma", MID, 3, 40, "layer"),      # two-wave workgroups, scores in registers
+    ("mfma", MID, 2, 64, "model"),      # few-token route
+    ("mfma", MID, 9, 128, "model"),
+    ("mfma", MID, 8, 200, "whole"),     # eight key blocks in registers, every layer's working buffer
+    ("mfma", MID, 48, 128, "model"),    # four-wave workgroups
+    ("mfma", MID, 7, 300, "whole"),     # online softmax
+    ("mfma", MID, 2, 512, "model"),
+])
+def test_padded_sequences_match_the_reference(gpu, oracle_mod, prec, dims, B, L, route):
+    """Keys beyond a sequence's length take no attention weight (all rows compared, padded ones
+    included); full lengths give the bits of the plain entry point; the mask matters at this scale."""
+    torch = gpu[0]
+    n_layers = 1 if route == "layer" else 2
+    wl = S.small_workload(8000 + L, dims, n_layers, B, L, n_absent=1)
+    S.make_every_term_matter(wl, 3, amp=6.0 if dims is MID else 3.0)
+    lens = _key_lengths(L, B, L)
+    want = oracle_mod.model_forward(dims, wl.shards, wl.params, wl.x, key_lengths=lens)
+    got = _run_masked(gpu, wl, prec, lens, route)
+    assert rel_err(got.float().cpu().numpy(), want) <= TOL[prec]
+    plain = _run_masked(gpu, wl, prec, None, route)
+    assert rel_err(plain.float().cpu().numpy(), want) > 3 * TOL[prec]
+    full = _run_masked(gpu, wl, prec, np.full(B, L, dtype=np.int32), route)
+    assert torch.equal(full, plain)
+
+
+def test_padded_sequences_ignore_what_the_padding_holds(gpu):
+    """Real rows come out bit for bit the same whatever finite values the padded rows of x hold, and
+    lengths outside 1..seq are clamped."""
+    torch, P, D = gpu
+    B, L = 6, 96
+    wl = S.small_workload(8100, MID, 2, B, L, n_absent=1, io_dtype="f16")
+    S.make_every_term_matter(wl, 4)
+    lens = _key_lengths(L, B, 1)
+    a = _run_masked(gpu, wl, "mfma", lens, "model")
+    rng = np.random.default_rng(2)
+    for b, n in enumerate(lens):
+        wl.x[b, n:] = rng.normal(0, 30, wl.x[b, n:].shape).astype(wl.x.dtype)
+    bb = _run_masked(gpu, wl, "mfma", lens, "model")
+    for b, n in enumerate(lens):
+        assert torch.equal(a[b, :n], bb[b, :n]), b
+    wild = lens.copy()
+    wild[0], wild[1] = L + 1000, -5            # clamped to L and to 1
+    assert lens[0] == L and lens[1] == 1
+    assert torch.equal(_run_masked(gpu, wl, "mfma", wild, "model"), bb)

@@ -326,3 +326,30 @@ def test_pipeline_rejected_calls_write_nothing_and_keep_the_preload_buffer(gpu, 
     assert torch.equal(y, ref)
     assert st["shards_hit"] == n_res and st["bytes_copied"] == total - b_res
     rig.pipe.close()
+
+
+@pytest.mark.parametrize("prec", ["f32", "mfma"])
+def test_pipeline_padded_sequences(gpu, oracle_mod, prec):
+    """sti_pipeline_forward_masked gives the bits of sti_model_forward_masked (and the oracle's
+    values), cold and warm."""
+    torch, P, D = gpu
+    dims = SMALL if prec == "f32" else MID
+    B, L = 5, 70
+    wl = S.small_workload(91, dims, 3, B, L, n_absent=1)
+    S.make_every_term_matter(wl, 9, amp=3.0)
+    total = sum(plan_bytes(dims, wl.plan))
+    rig = Rig(gpu, wl, prec, preload_bytes=total // 3)
+    lens = np.array([L, 1, 33, 64, 17], dtype=np.int32)
+    ld = torch.from_numpy(lens).cuda()
+    ref = torch.full_like(rig.x, float("nan"))
+    P.sti_model_forward_masked(dims, rig.dev_store, rig.params, wl.plan, rig.x, ref, ld, rig.precision, rig.ws)
+    torch.cuda.synchronize()
+    want = oracle_mod.model_forward(dims, wl.shards, wl.params, wl.x, key_lengths=lens)
+    assert rel_err(ref.float().cpu().numpy(), want) <= TOL[prec]
+    for _ in range(2):
+        y = torch.full_like(rig.x, float("nan"))
+        rig.pipe.forward(rig.host_store, rig.params, wl.plan, rig.x, y, rig.precision, rig.ws, key_lengths=ld)
+        torch.cuda.synchronize()
+        assert torch.equal(y, ref)
+    assert not torch.equal(rig.run()[0], ref)      # the plain call differs
+    rig.pipe.close()
