@@ -587,10 +587,6 @@ sti_status sti_decode_shards(const sti_shard *shards, int n_shards, uint64_t wei
     return e == hipSuccess ? STI_OK : STI_ERR_HIP;
 }
 
-}  // extern "C"
-
-extern "C" {
-
 size_t sti_workspace_bytes(const sti_dims *dims, int batch, int seq, sti_precision precision)
 {
     if (check_dims(dims, batch, seq, precision) != STI_OK) return 0;
