@@ -702,3 +702,37 @@ def test_padded_sequences_ignore_what_the_padding_holds(gpu):
     wild[0], wild[1] = L + 1000, -5            # clamped to L and to 1
     assert lens[0] == L and lens[1] == 1
     assert torch.equal(_run_masked(gpu, wl, "mfma", wild, "model"), bb)
+
+
+def test_captured_masked_forward_follows_the_lengths_in_device_memory(gpu):
+    """The key lengths are read by the kernels, not by the host: a graph captured once serves
+    other lengths by rewriting the device array between replays."""
+    torch, P, D = gpu
+    B, L = 3, 60
+    wl = S.small_workload(889, MID, 2, B, L, n_absent=1, io_dtype="f16")
+    S.make_every_term_matter(wl, 6)
+    prec = P.STI_PREC_F16_MFMA
+    shards, params, x = D.upload_workload(wl)
+    store = P.make_store(D.store_from_plan(shards))
+    ws = torch.empty(P.sti_workspace_bytes(MID, B, L, prec), dtype=torch.uint8, device="cuda")
+    lens = torch.tensor([L, 7, 33], dtype=torch.int32, device="cuda")
+    y_graph = torch.full_like(x, float("nan"))
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            P.sti_model_forward_masked(MID, store, params, wl.plan, x, y_graph, lens, prec, ws)
+    torch.cuda.synchronize()
+    seen = []
+    for new in ([L, 7, 33], [1, L, 32], [59, 31, 2], [L, 7, 33]):
+        lens.copy_(torch.tensor(new, dtype=torch.int32))
+        y_graph.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        eager = torch.full_like(x, float("nan"))
+        P.sti_model_forward_masked(MID, store, params, wl.plan, x, eager, lens, prec, ws)
+        torch.cuda.synchronize()
+        assert torch.equal(y_graph, eager), new
+        seen.append(eager.clone())
+    assert not torch.equal(seen[0], seen[1]) and torch.equal(seen[0], seen[3])
