@@ -736,3 +736,19 @@ def test_captured_masked_forward_follows_the_lengths_in_device_memory(gpu):
         assert torch.equal(y_graph, eager), new
         seen.append(eager.clone())
     assert not torch.equal(seen[0], seen[1]) and torch.equal(seen[0], seen[3])
+
+
+def test_padded_sequences_at_configuration_4_size(gpu, oracle_mod):
+    """32 x 128 tokens of BERT-base (three layers, whole-model route, the launch shapes the
+    benchmark times) with a length mix from 1 to 128: sampled sequences against the reference,
+    each run alone at its padded length."""
+    wl = S.config4(n_layers=3)
+    S.make_every_term_matter(wl, 4, amp=3.0)
+    rng = np.random.default_rng(12)
+    lens = rng.integers(1, wl.seq + 1, wl.x.shape[0]).astype(np.int32)
+    lens[0], lens[31], lens[7] = wl.seq, 1, 65
+    got = _run_masked(gpu, wl, "mfma", lens, "whole").float().cpu().numpy()
+    assert np.all(np.isfinite(got))
+    for b in (0, 7, 19, 31):
+        want = oracle_mod.model_forward(wl.dims, wl.shards, wl.params, wl.x[b:b + 1], key_lengths=lens[b:b + 1])
+        assert rel_err(got[b:b + 1], want) <= TOL["mfma"], (b, int(lens[b]))
