@@ -244,16 +244,16 @@ hipError_t launch_attention_mfma(const void *qkv, void *ctx, int B, int L, int m
     if (dh != DH) return hipErrorInvalidValue;
     const int Lp = (L + 31) / 32 * 32;
     const size_t lds = ((size_t)Lp * KPAD + (size_t)DH * (Lp + 8)) * sizeof(_Float16);
-    static bool attr_set = false;
-    if (!attr_set) {
+    // once per process, and safe when several host threads make their first call together
+    static const hipError_t attr_status = [] {
         hipError_t e = hipFuncSetAttribute((const void *)attention_mfma_kernel<4, 0>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e == hipSuccess)
             e = hipFuncSetAttribute((const void *)attention_mfma_kernel<2, 0>,
                                     hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+        return e;
+    }();
+    if (attr_status != hipSuccess) return attr_status;
     // few (sequence, head) pairs: 64 queries per workgroup put twice as many workgroups on the chip
     const bool small_wg = (int64_t)B * m * ((L + 127) / 128) < 128 && L > 32;
     if (small_wg) {

@@ -212,14 +212,12 @@ hipError_t launch_ra(const GemmProblem &p, const GemmBlocks &blocks, int N, int 
                      int64_t partial_stride, hipStream_t stream)
 {
     dim3 grid(N / 32, k_splits, (p.T + ROWS - 1) / ROWS);
-    static bool attr_set = false;   // more than 64 KiB of dynamic LDS needs an explicit opt-in
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)gemm_skinny_kernel<RA>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize,
-                                           (int)sizeof(SkinnySmem<RA>));
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    // more than 64 KiB of dynamic LDS needs an explicit opt-in: once per instantiation, and safe
+    // when several host threads make their first call together
+    static const hipError_t attr_status =
+        hipFuncSetAttribute((const void *)gemm_skinny_kernel<RA>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)sizeof(SkinnySmem<RA>));
+    if (attr_status != hipSuccess) return attr_status;
     launch((gemm_skinny_kernel<RA>), grid, dim3(NW * 64), sizeof(SkinnySmem<RA>), stream, p, blocks, k_splits,
                                                                               partial_stride);
     return hipGetLastError();

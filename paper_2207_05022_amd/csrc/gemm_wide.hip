@@ -425,13 +425,11 @@ hipError_t launch_variant(const GemmProblem &p, const GemmBlocks &blocks, int N,
 {
     constexpr int BM = RA * 32, BN = NW * 32;
     constexpr size_t lds = wide_lds_bytes<RA, NW, KS>();
-    static bool attr_set = false;   // per instantiation
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)gemm_wide_kernel<KIND, RA, NW, KS, EARLY>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    // once per instantiation, and safe when several host threads make their first call together
+    static const hipError_t attr_status =
+        hipFuncSetAttribute((const void *)gemm_wide_kernel<KIND, RA, NW, KS, EARLY>,
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (attr_status != hipSuccess) return attr_status;
     const int total = ((N + BN - 1) / BN) * ((p.T + BM - 1) / BM);
     const bool n_split = (KIND == GEMM_QKV || KIND == GEMM_FFN_UP);
     dim3 grid(((total + 7) / 8) * 8, (!n_split && p.k_splits > 1) ? p.k_splits : 1);
