@@ -10,6 +10,7 @@ import numpy as np
 import pytest
 
 import sti_synth as S
+from parity import assert_parity
 
 pytestmark = pytest.mark.gpu
 
@@ -26,9 +27,6 @@ def gpu():
     assert torch.cuda.is_available(), "needs a GPU"
     return torch, P, D
 
-
-def rel_err(got, want):
-    return float(np.max(np.abs(got.astype(np.float64) - want)) / max(np.max(np.abs(want)), 1e-30))
 
 
 def shard_bytes(dims, k):
@@ -102,7 +100,7 @@ def test_pipeline_matches_model_forward_and_oracle(gpu, oracle_mod, prec, dims, 
 
     y, st = rig.run()                      # cold: everything crosses the host link
     assert torch.equal(y, ref)
-    assert rel_err(y.float().cpu().numpy(), want) <= TOL[prec]
+    assert_parity(y.float().cpu().numpy(), want, TOL[prec])
     assert st["bytes_copied"] == total and st["shards_copied"] == len(plan_bytes(dims, wl.plan))
     assert st["shards_hit"] == 0
     assert st["shards_preloaded"] == n_res and st["bytes_resident"] == b_res
@@ -124,7 +122,7 @@ def test_pipeline_without_preload_buffer(gpu, oracle_mod):
         assert torch.equal(y, ref)
         assert st["shards_hit"] == 0 and st["shards_preloaded"] == 0
         assert st["bytes_copied"] == sum(plan_bytes(MID, wl.plan))
-    assert rel_err(y.float().cpu().numpy(), oracle_mod.model_forward(MID, wl.shards, wl.params, wl.x)) <= TOL["mfma"]
+    assert_parity(y.float().cpu().numpy(), oracle_mod.model_forward(MID, wl.shards, wl.params, wl.x), TOL["mfma"])
     rig.pipe.close()
 
 
@@ -189,7 +187,7 @@ def test_pipeline_plan_change_invalidates_from_the_changed_shard(gpu, oracle_mod
     shards = [list(r) for r in wl_a.shards]
     shards[1][0] = wl_b.shards[1][0]
     want = oracle_mod.model_forward(dims, shards, wl_a.params, wl_a.x)
-    assert rel_err(y.float().cpu().numpy(), want) <= TOL["mfma"]
+    assert_parity(y.float().cpu().numpy(), want, TOL["mfma"])
     y, st = rig.run(plan=plan_b, store=host_store)
     assert torch.equal(y, ref_b) and st["bytes_copied"] == 0
     rig.pipe.close()
@@ -222,7 +220,7 @@ def test_pipeline_outliers_and_io_dtypes(gpu, oracle_mod):
     y, _ = rig.run()
     assert torch.equal(y, rig.reference())
     want = oracle_mod.model_forward(MID, wl.shards, wl.params, wl.x)
-    assert rel_err(y.float().cpu().numpy(), want) <= TOL["mfma"]
+    assert_parity(y.float().cpu().numpy(), want, TOL["mfma"])
     rig.pipe.close()
 
 
@@ -241,7 +239,7 @@ def test_pipeline_config2_full_size(gpu, oracle_mod):
     n_res, b_res = expected_resident(wl.dims, wl.plan, 8 << 20)
     assert st2["shards_hit"] == n_res > 0 and st2["bytes_copied"] == st["bytes_copied"] - b_res
     want = oracle_mod.model_forward(wl.dims, wl.shards, wl.params, wl.x)
-    assert rel_err(y.float().cpu().numpy(), want) <= TOL["mfma"]
+    assert_parity(y.float().cpu().numpy(), want, TOL["mfma"])
     rig.pipe.close()
 
 
@@ -345,7 +343,7 @@ def test_pipeline_padded_sequences(gpu, oracle_mod, prec):
     P.sti_model_forward_masked(dims, rig.dev_store, rig.params, wl.plan, rig.x, ref, ld, rig.precision, rig.ws)
     torch.cuda.synchronize()
     want = oracle_mod.model_forward(dims, wl.shards, wl.params, wl.x, key_lengths=lens)
-    assert rel_err(ref.float().cpu().numpy(), want) <= TOL[prec]
+    assert_parity(ref.float().cpu().numpy(), want, TOL[prec])
     for _ in range(2):
         y = torch.full_like(rig.x, float("nan"))
         rig.pipe.forward(rig.host_store, rig.params, wl.plan, rig.x, y, rig.precision, rig.ws, key_lengths=ld)
