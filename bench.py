@@ -135,7 +135,7 @@ def bench_decode(P, torch, S, steps, warmup):
     cbs = torch.from_numpy(cb_host).cuda()
     shards = [SimpleNamespace(bitwidth=int(ds.bitwidths[s]), data=packed[int(ds.offsets[s]):], codebook=cbs[s])
               for s in range(ds.n_shards)]
-    arr = P.binding._shard_array(shards)
+    arr = P.shard_array(shards)
     out = torch.empty(ds.n_shards * n, dtype=torch.float16, device="cuda")
     ws = torch.empty(max(16, P.sti_decode_workspace_bytes(ds.n_shards)), dtype=torch.uint8, device="cuda")
     for _ in range(warmup):

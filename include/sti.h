@@ -74,9 +74,13 @@ typedef enum { STI_F32 = 0, STI_F16 = 1, STI_BF16 = 2 } sti_dtype;
 /* STI_PREC_F32: float32 storage and arithmetic end to end (decode to a float32
  *   working buffer, then float32 kernels); any dimensions.
  * STI_PREC_F16_MFMA: binary16 operands on the matrix cores with float32
- *   accumulation, decode fused into the weight loader; needs d_head == 64,
- *   d_model and ffn_per_shard multiples of 64 and seq <= 512 (STI_ERR_DIMS
- *   otherwise). */
+ *   accumulation.  Up to 128 tokens per call (192 when d_model <= 768) the
+ *   projections decode the packed streams inside their weight loader; with
+ *   more tokens, and for shards that carry an outlier dictionary, a layer's
+ *   shards are decompressed once into a binary16 working buffer in the
+ *   workspace that the projections then read (every weight would otherwise be
+ *   decoded once per 64 or 128 token rows).  Needs d_head == 64, d_model and
+ *   ffn_per_shard multiples of 64 and seq <= 512 (STI_ERR_DIMS otherwise). */
 typedef enum { STI_PREC_F32 = 0, STI_PREC_F16_MFMA = 1 } sti_precision;
 
 typedef struct {
@@ -133,9 +137,15 @@ const char *sti_status_string(sti_status s);
  *  workspace         DEVICE scratch of at least sti_decode_workspace_bytes(n_shards)
  *                    bytes, 16-byte aligned; may be NULL when that size is 0.
  *
+ * Stream capture: a call with at most 64 shards enqueues kernels only and may be
+ * captured into a graph.  A larger call uploads its shard table through a pinned
+ * host buffer that later calls reuse, so it returns STI_ERR_UNSUPPORTED, before
+ * enqueuing anything, when `hip_stream` is capturing.
+ *
  * Errors: NULL / DIMS (negative counts) / BITWIDTH / MISSING_SHARD (data NULL,
  * or codebook NULL for k <= 6) / NULL (outlier arrays missing) / ALIGN /
- * WORKSPACE / DTYPE / UNSUPPORTED (outliers on a 32-bit shard) / HIP.
+ * WORKSPACE / DTYPE / UNSUPPORTED (outliers on a 32-bit shard; more than 64
+ * shards under stream capture) / HIP.
  * ------------------------------------------------------------------------- */
 size_t sti_decode_workspace_bytes(int n_shards);
 
@@ -170,6 +180,37 @@ sti_status sti_layer_forward(const sti_dims *dims, const sti_shard *shards,
                              const sti_layer_params *params, const void *x, void *y,
                              sti_dtype io_dtype, int batch, int seq, sti_precision precision,
                              void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* ---------------------------------------------------------------------------
+ * The working buffer of the matrix-core path by itself (Section "Submodel execution":
+ * all selected shards of a layer are decompressed into a working buffer before the
+ * layer's computation starts).  sti_decode_working_buffer writes what sti_layer_forward
+ * (STI_PREC_F16_MFMA, working-buffer route) places in its workspace before the
+ * projections run: the present shards, in slot order, compacted, each as
+ * weights_per_shard = d*(4*dh + 2*f) binary16 values (codebook entries and outlier
+ * weights rounded to nearest even), in a tiled order chosen so that one matrix-core
+ * operand of a wave is one contiguous 1 KiB read:
+ *
+ *   weight j of a shard lies in one of the six row-major sub-blocks Wq|Wk|Wv [3dh x d],
+ *   Wo [d x dh], W1 [f x d], W2 [d x f] (element offsets 0, 3*dh*d, 4*dh*d,
+ *   4*dh*d + f*d; Wq, Wk, Wv form one block of 3*dh rows), at (row, col) of a block with
+ *   C columns that starts at element offset `sub`.  Its place in the shard's image is
+ *     sub + ((row/32)*(C/64) + col/64)*2048 + ((col%32)/8)*512
+ *         + (((col%64)/32)*32 + row%32)*8 + col%8            (binary16 elements).
+ *
+ * sti_working_buffer_offset evaluates that formula (HOST; -1 for invalid dims or j out of
+ * range); sti_working_buffer_bytes is the size for all M shards present (0 for invalid dims).
+ * Dimensions as for STI_PREC_F16_MFMA.
+ *
+ *  shards    HOST array [M]; bitwidth 0 = absent (skipped, nothing written for it).
+ *  out       DEVICE, 256-byte aligned, at least (present shards) * weights_per_shard * 2 bytes.
+ * Errors: NULL / DIMS / BITWIDTH / MISSING_SHARD / ALIGN / WORKSPACE (out_bytes too small) / HIP.
+ * Kernel launches only: may be captured.
+ * ------------------------------------------------------------------------- */
+size_t sti_working_buffer_bytes(const sti_dims *dims);
+int64_t sti_working_buffer_offset(const sti_dims *dims, uint64_t j);
+sti_status sti_decode_working_buffer(const sti_dims *dims, const sti_shard *shards, void *out,
+                                     size_t out_bytes, void *hip_stream);
 
 /* ---------------------------------------------------------------------------
  * Layers 0 .. n_layers-1 in order, the output of one feeding the next (Section
@@ -225,7 +266,10 @@ sti_status sti_model_forward_masked(const sti_dims *dims, int n_layers, const st
  * the layer goes through the working buffer (more than 128 tokens, more than 192 when
  * d_model <= 768); otherwise, and for n_layers <= 1, it equals sti_workspace_bytes.
  * sti_model_forward takes the grouped route whenever workspace_bytes is at least this value
- * and the per-layer route otherwise: same results either way.  0 on invalid arguments. */
+ * and the per-layer route otherwise: same results either way.  The grouped route uploads
+ * a shard table through a pinned host buffer that later calls reuse and is therefore
+ * never taken while `hip_stream` is capturing: a captured call runs the per-layer route
+ * (kernel launches only), whatever the workspace size.  0 on invalid arguments. */
 size_t sti_model_workspace_bytes(const sti_dims *dims, int n_layers, int batch, int seq,
                                  sti_precision precision);
 

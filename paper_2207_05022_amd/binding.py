@@ -76,27 +76,33 @@ def _load():
     L.sti_decode_shards.restype = C.c_int
     L.sti_decode_shards.argtypes = [C.POINTER(StiShard), C.c_int, C.c_uint64, C.c_void_p, C.c_int,
                                     C.c_void_p, C.c_size_t, C.c_void_p]
-    if hasattr(L, "sti_workspace_bytes"):
-        L.sti_workspace_bytes.restype = C.c_size_t
-        L.sti_workspace_bytes.argtypes = [C.POINTER(StiDims), C.c_int, C.c_int, C.c_int]
-        L.sti_layer_forward.restype = C.c_int
-        L.sti_layer_forward.argtypes = [
-            C.POINTER(StiDims), C.POINTER(StiShard), C.POINTER(StiLayerParams), C.c_void_p,
-            C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_size_t, C.c_void_p]
-        L.sti_layer_forward_masked.restype = C.c_int
-        L.sti_layer_forward_masked.argtypes = [
-            C.POINTER(StiDims), C.POINTER(StiShard), C.POINTER(StiLayerParams), C.c_void_p,
-            C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_int, C.c_void_p, C.c_size_t, C.c_void_p]
-        L.sti_model_forward_masked.restype = C.c_int
-        L.sti_model_forward_masked.argtypes = [
-            C.POINTER(StiDims), C.c_int, C.POINTER(StiShard), C.POINTER(StiLayerParams),
-            C.POINTER(C.c_int8), C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_int,
-            C.c_void_p, C.c_size_t, C.c_void_p]
-        L.sti_model_forward.restype = C.c_int
-        L.sti_model_forward.argtypes = [
-            C.POINTER(StiDims), C.c_int, C.POINTER(StiShard), C.POINTER(StiLayerParams),
-            C.POINTER(C.c_int8), C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int,
-            C.c_void_p, C.c_size_t, C.c_void_p]
+    L.sti_workspace_bytes.restype = C.c_size_t
+    L.sti_workspace_bytes.argtypes = [C.POINTER(StiDims), C.c_int, C.c_int, C.c_int]
+    L.sti_layer_forward.restype = C.c_int
+    L.sti_layer_forward.argtypes = [
+        C.POINTER(StiDims), C.POINTER(StiShard), C.POINTER(StiLayerParams), C.c_void_p,
+        C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_size_t, C.c_void_p]
+    L.sti_layer_forward_masked.restype = C.c_int
+    L.sti_layer_forward_masked.argtypes = [
+        C.POINTER(StiDims), C.POINTER(StiShard), C.POINTER(StiLayerParams), C.c_void_p,
+        C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_int, C.c_void_p, C.c_size_t, C.c_void_p]
+    L.sti_model_forward_masked.restype = C.c_int
+    L.sti_model_forward_masked.argtypes = [
+        C.POINTER(StiDims), C.c_int, C.POINTER(StiShard), C.POINTER(StiLayerParams),
+        C.POINTER(C.c_int8), C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_int,
+        C.c_void_p, C.c_size_t, C.c_void_p]
+    L.sti_model_forward.restype = C.c_int
+    L.sti_model_forward.argtypes = [
+        C.POINTER(StiDims), C.c_int, C.POINTER(StiShard), C.POINTER(StiLayerParams),
+        C.POINTER(C.c_int8), C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int,
+        C.c_void_p, C.c_size_t, C.c_void_p]
+    L.sti_working_buffer_bytes.restype = C.c_size_t
+    L.sti_working_buffer_bytes.argtypes = [C.POINTER(StiDims)]
+    L.sti_working_buffer_offset.restype = C.c_int64
+    L.sti_working_buffer_offset.argtypes = [C.POINTER(StiDims), C.c_uint64]
+    L.sti_decode_working_buffer.restype = C.c_int
+    L.sti_decode_working_buffer.argtypes = [C.POINTER(StiDims), C.POINTER(StiShard), C.c_void_p, C.c_size_t,
+                                            C.c_void_p]
     L.sti_quantize_workspace_bytes.restype = C.c_size_t
     L.sti_quantize_workspace_bytes.argtypes = [C.POINTER(StiDims)]
     L.sti_quantize_layer.restype = C.c_int
@@ -179,7 +185,9 @@ def make_params(p) -> StiLayerParams:
     return StiLayerParams(*[_ptr(getattr(p, n)) for n, _ in StiLayerParams._fields_])
 
 
-def _shard_array(shards: Sequence) -> "C.Array":
+def shard_array(shards: Sequence) -> "C.Array":
+    """HOST array of sti_shard from shard objects (.bitwidth/.data/.codebook CUDA tensors, optional
+    .outlier_pos/.outlier_val; None = absent).  Building it once saves the marshalling per call."""
     if isinstance(shards, C.Array):
         return shards
     arr = (StiShard * max(1, len(shards)))()
@@ -202,12 +210,32 @@ def sti_decode_shards(shards: Sequence, weights_per_shard: int, out, workspace=N
                       stream=None) -> None:
     """Decode ``shards`` into ``out`` (CUDA tensor of float32/float16/bfloat16 with
     len(shards) * weights_per_shard elements)."""
-    arr = _shard_array(shards)
+    arr = shard_array(shards)
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     st = lib.sti_decode_shards(arr, len(shards), int(weights_per_shard), _ptr(out),
                                _dtype_code(out), _ptr(workspace), ws_bytes, _stream_handle(stream))
     if st != 0:
         raise StiError(st, "sti_decode_shards")
+
+
+def sti_working_buffer_bytes(dims) -> int:
+    d = make_dims(dims)
+    return int(lib.sti_working_buffer_bytes(C.byref(d)))
+
+
+def sti_working_buffer_offset(dims, j: int) -> int:
+    d = make_dims(dims)
+    return int(lib.sti_working_buffer_offset(C.byref(d), int(j)))
+
+
+def sti_decode_working_buffer(dims, shards: Sequence, out, stream=None) -> None:
+    """shards: M entries, None = absent; out: CUDA float16 tensor for the present shards' images."""
+    d = make_dims(dims)
+    arr = shard_array(shards)
+    st = lib.sti_decode_working_buffer(C.byref(d), arr, _ptr(out), out.numel() * out.element_size(),
+                                       _stream_handle(stream))
+    if st != 0:
+        raise StiError(st, "sti_decode_working_buffer")
 
 
 def sti_workspace_bytes(dims, batch: int, seq: int, precision: int) -> int:
@@ -234,7 +262,7 @@ def sti_layer_forward(dims, shards: Sequence, params, x, y, precision: int, work
                       stream=None) -> None:
     """x, y: CUDA tensors [batch, seq, d_model] of one dtype; shards: M entries, None = absent."""
     d = make_dims(dims)
-    arr = _shard_array(shards)
+    arr = shard_array(shards)
     p = make_params(params)
     batch, seq = int(x.shape[0]), int(x.shape[1])
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
@@ -249,7 +277,7 @@ def sti_layer_forward_masked(dims, shards: Sequence, params, x, y, key_lengths, 
                              workspace, stream=None) -> None:
     """As sti_layer_forward; key_lengths: CUDA int32 tensor [batch], real positions per sequence."""
     d = make_dims(dims)
-    arr = _shard_array(shards)
+    arr = shard_array(shards)
     p = make_params(params)
     batch, seq = int(x.shape[0]), int(x.shape[1])
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()

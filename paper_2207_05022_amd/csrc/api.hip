@@ -163,6 +163,17 @@ LaunchEvents take_launch_events()
     return ev;
 }
 
+// Whether `stream` is recording a graph.  The staging ring (a pinned slot that later calls
+// overwrite, an event the host waits on) must not be recorded: a replay would read whatever
+// table the slot holds by then.
+inline hipError_t stream_is_capturing(hipStream_t stream, bool *capturing)
+{
+    hipStreamCaptureStatus status = hipStreamCaptureStatusNone;
+    const hipError_t e = hipStreamIsCapturing(stream, &status);
+    *capturing = (status != hipStreamCaptureStatusNone);
+    return e;
+}
+
 inline ShardDesc make_desc(const sti_shard &s, int tag)
 {
     return ShardDesc{s.data, s.codebook, s.bitwidth, tag, s.outlier_pos, s.outlier_val, s.n_outliers, 0};
@@ -543,14 +554,18 @@ sti_status sti_decode_shards(const sti_shard *shards, int n_shards, uint64_t wei
         if (st != STI_OK) return st;
     }
     const size_t need = sti_decode_workspace_bytes(n_shards);
+    hipStream_t stream = (hipStream_t)hip_stream;
+    hipError_t e;
     if (need) {
         if (!workspace || workspace_bytes < need) return STI_ERR_WORKSPACE;
         if (!aligned(workspace, 16)) return STI_ERR_ALIGN;
+        // the table of a large call is uploaded through the staging ring: not under capture
+        bool capturing = false;
+        if (stream_is_capturing(stream, &capturing) != hipSuccess) return STI_ERR_HIP;
+        if (capturing) return STI_ERR_UNSUPPORTED;
     }
     if (weights_per_shard == 0) return STI_OK;
 
-    hipStream_t stream = (hipStream_t)hip_stream;
-    hipError_t e;
     uint32_t max_outliers = 0;
     for (int s = 0; s < n_shards; ++s)
         if (shards[s].n_outliers > max_outliers) max_outliers = shards[s].n_outliers;
@@ -585,6 +600,61 @@ sti_status sti_decode_shards(const sti_shard *shards, int n_shards, uint64_t wei
                                       out_dtype, stream);
     }
     return e == hipSuccess ? STI_OK : STI_ERR_HIP;
+}
+
+size_t sti_working_buffer_bytes(const sti_dims *dims)
+{
+    if (check_dims(dims, 0, 0, STI_PREC_F16_MFMA) != STI_OK) return 0;
+    return (size_t)dims->n_heads * dims->d_model * (4 * (size_t)dims->d_head + 2 * (size_t)dims->ffn_per_shard) * 2;
+}
+
+int64_t sti_working_buffer_offset(const sti_dims *dims, uint64_t j)
+{
+    if (check_dims(dims, 0, 0, STI_PREC_F16_MFMA) != STI_OK) return -1;
+    const uint64_t d = dims->d_model, dh = dims->d_head, f = dims->ffn_per_shard;
+    if (j >= d * (4 * dh + 2 * f)) return -1;
+    const uint64_t o_o = 3 * dh * d, o_1 = 4 * dh * d, o_2 = o_1 + f * d;
+    uint64_t sub, cols;
+    if (j < o_o) { sub = 0; cols = d; }
+    else if (j < o_1) { sub = o_o; cols = dh; }
+    else if (j < o_2) { sub = o_1; cols = d; }
+    else { sub = o_2; cols = f; }
+    const uint64_t row = (j - sub) / cols, col = (j - sub) % cols;
+    const uint64_t cell = (row / 32) * (cols / 64) + col / 64;
+    const uint64_t lane = ((col % 64) / 32) * 32 + row % 32, q = (col % 32) / 8;
+    return (int64_t)(sub + cell * 2048 + q * 512 + lane * 8 + col % 8);
+}
+
+sti_status sti_decode_working_buffer(const sti_dims *dims, const sti_shard *shards, void *out,
+                                     size_t out_bytes, void *hip_stream)
+{
+    sti_status st = check_dims(dims, 0, 0, STI_PREC_F16_MFMA);
+    if (st != STI_OK) return st;
+    if (!shards) return STI_ERR_NULL;
+    const int M = dims->n_heads;
+    InlineShardTable t;
+    memset(&t, 0, sizeof(t));
+    int m = 0;
+    uint32_t max_outliers = 0;
+    for (int i = 0; i < M; ++i) {
+        st = check_layer_shard(shards[i]);
+        if (st != STI_OK) return st;
+        if (shards[i].bitwidth == 0) continue;
+        if (shards[i].n_outliers > max_outliers) max_outliers = shards[i].n_outliers;
+        t.d[m++] = make_desc(shards[i], i);
+    }
+    if (m == 0) return STI_OK;
+    const size_t wsh = (size_t)dims->d_model * (4 * (size_t)dims->d_head + 2 * (size_t)dims->ffn_per_shard);
+    if (!out) return STI_ERR_NULL;
+    if (out_bytes < (size_t)m * wsh * 2) return STI_ERR_WORKSPACE;
+    if (!aligned(out, 256)) return STI_ERR_ALIGN;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    STI_TRY(timed(STI_K_DECODE, stream, [&] {
+        return launch_decode_tiled(t, m, dims->d_model, dims->d_head, dims->ffn_per_shard, out, stream);
+    }));
+    STI_TRY(launch_patch_outliers_tiled(t, m, max_outliers, dims->d_model, dims->d_head, dims->ffn_per_shard,
+                                        out, stream));
+    return STI_OK;
 }
 
 size_t sti_workspace_bytes(const sti_dims *dims, int batch, int seq, sti_precision precision)
@@ -685,15 +755,22 @@ sti_status model_forward(const sti_dims *dims, int n_layers, const sti_shard *st
     // decompressed a few layers per launch (below); otherwise each layer decompresses into the
     // one buffer just before it runs.
     WorkspaceLayout wl = workspace_layout(*dims, T, precision);
-    const bool whole_model_fits =
-        precision == STI_PREC_F16_MFMA && !few_token_path(*dims, T) && n_layers > 1 &&
-        workspace_bytes >= workspace_layout(*dims, T, precision, n_layers).total;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    // (under stream capture the grouped route, whose shard table goes through the staging
+    //  ring, is not taken: the per-layer route records kernel launches only)
+    bool whole_model_fits =
+        precision == STI_PREC_F16_MFMA && !few_token_path(*dims, T) && n_layers > 1 && workspace &&
+        aligned(workspace, 256) && workspace_bytes >= workspace_layout(*dims, T, precision, n_layers).total;
+    if (whole_model_fits) {
+        bool capturing = false;
+        if (stream_is_capturing(stream, &capturing) != hipSuccess) return STI_ERR_HIP;
+        if (capturing) whole_model_fits = false;
+    }
     if (whole_model_fits) wl = workspace_layout(*dims, T, precision, n_layers);
     if (!workspace || workspace_bytes < wl.total) return STI_ERR_WORKSPACE;
     if (!aligned(workspace, 256)) return STI_ERR_ALIGN;
     if (T == 0) return STI_OK;
 
-    hipStream_t stream = (hipStream_t)hip_stream;
     uint8_t *ws = (uint8_t *)workspace;
     const size_t io_bytes = (size_t)T * dims->d_model * (io_dtype == STI_F32 ? 4 : 2);
     if (n_layers == 0) {

@@ -213,3 +213,29 @@ def test_quantizer_argument_errors(P):
     assert q(*args(reg=-1.0)) == 2 and q(*args(thr=float("nan"))) == 2
     assert q(*args(w=FAKE + 4)) == 5
     assert q(*args(ws=None)) == 6 and q(*args(wsb=1024)) == 6
+
+
+def test_working_buffer_layout_is_a_permutation_of_the_shard(P):
+    """Host arithmetic only: every weight of a shard has a place of its own inside the shard's image,
+    sub-blocks stay inside their own range, and 8 consecutive columns stay consecutive."""
+    import sti_synth as S
+    dims = S.Dims(128, 3, 64, 192, 1e-12)
+    n = dims.weights_per_shard
+    d = P.binding.make_dims(dims)
+    off = np.array([P.lib.sti_working_buffer_offset(C.byref(d), j) for j in range(n)])
+    assert np.array_equal(np.sort(off), np.arange(n))
+    bounds = [0, 3 * 64 * 128, 4 * 64 * 128, 4 * 64 * 128 + 192 * 128, n]
+    for a, b in zip(bounds[:-1], bounds[1:]):
+        assert off[a:b].min() == a and off[a:b].max() == b - 1
+    assert np.all(np.diff(off.reshape(-1, 8), axis=1) == 1)
+    assert P.lib.sti_working_buffer_offset(C.byref(d), n) == -1
+    bad = P.binding.make_dims(S.Dims(100, 3, 64, 192, 1e-12))
+    assert P.lib.sti_working_buffer_offset(C.byref(bad), 0) == -1
+    assert P.lib.sti_working_buffer_bytes(C.byref(bad)) == 0
+    assert P.lib.sti_working_buffer_bytes(C.byref(d)) == 3 * n * 2
+    arr = (P.StiShard * 3)(shard(P, 4), shard(P, 0), shard(P, 9))
+    assert P.lib.sti_decode_working_buffer(C.byref(d), arr, FAKE, 1 << 30, None) == 3
+    arr = (P.StiShard * 3)(shard(P, 4), shard(P, 0), shard(P, 2))
+    assert P.lib.sti_decode_working_buffer(C.byref(d), arr, FAKE, 8, None) == 6
+    assert P.lib.sti_decode_working_buffer(C.byref(d), arr, None, 1 << 30, None) == 1
+    assert P.lib.sti_decode_working_buffer(C.byref(d), None, FAKE, 1 << 30, None) == 1

@@ -172,7 +172,7 @@ def test_config1_full_size_sampled_shards(gpu, oracle_mod):
               for s in range(ds.n_shards)]
     out = torch.full((ds.n_shards * n,), 7, dtype=torch.float16, device="cuda")
     ws = torch.empty(max(16, P.sti_decode_workspace_bytes(ds.n_shards)), dtype=torch.uint8, device="cuda")
-    P.sti_decode_shards(P.binding._shard_array(shards), n, out, ws)
+    P.sti_decode_shards(P.shard_array(shards), n, out, ws)
     torch.cuda.synchronize()
     out = out.view(ds.n_shards, n)
     sample = set()
@@ -234,3 +234,68 @@ def test_more_shards_than_a_grid_dimension_with_dictionaries(gpu, oracle_mod):
     torch.cuda.synchronize()
     got = out.view(torch.int16).cpu().numpy().view(np.uint16).reshape(n_shards, n)
     assert np.array_equal(got, want)
+
+
+# ------------------------------------------------------------------ working buffer of the matrix-core path
+
+def untile(image, dims):
+    """Logical order of one shard's binary16 image, from the layout the header documents (test-local:
+    sub-block, 32-row strip, 64-column tile, 8-column piece, lane = half-tile * 32 + row % 32)."""
+    d, dh, f = dims.d_model, dims.d_head, dims.ffn_per_shard
+    out = np.empty(dims.weights_per_shard, dtype=image.dtype)
+    sub = 0
+    for rows, cols in ((3 * dh, d), (d, dh), (f, d), (d, f)):
+        r, c = np.meshgrid(np.arange(rows), np.arange(cols), indexing="ij")
+        off = (sub + ((r // 32) * (cols // 64) + c // 64) * 2048 + ((c % 32) // 8) * 512
+               + (((c % 64) // 32) * 32 + r % 32) * 8 + c % 8)
+        out[sub:sub + rows * cols] = image[off.ravel()]
+        sub += rows * cols
+    return out
+
+
+@pytest.mark.parametrize("dims", [S.Dims(128, 7, 64, 64, 1e-12), S.BERT_BASE], ids=["small", "bert_base"])
+def test_working_buffer_is_the_reference_decode_bit_for_bit(gpu, oracle_mod, dims):
+    """The binary16 working buffer that every layer with many tokens multiplies from (and whose
+    per-lane loader the few-token projections share): every bitwidth incl. the 3- and 5-bit streams
+    whose indexes straddle dwords, an absent slot, outlier dictionaries."""
+    torch, P, D = gpu
+    rng = np.random.default_rng(97)
+    n = dims.weights_per_shard
+    bits = [2, 3, 4, 5, 6, 32, 0] + [int(b) for b in rng.choice([2, 3, 4, 5, 6, 32], dims.n_heads - 7)]
+    host = [None if b == 0 else S.make_shard(rng, n, b) for b in bits]
+    for s in host:
+        if s is not None and s.bitwidth != 32:
+            S.add_outliers(rng, s, n, 0.002)
+    present = [s for s in host if s is not None]
+    out = torch.full((len(present) * n,), float("nan"), dtype=torch.float16, device="cuda")
+    assert P.sti_working_buffer_bytes(dims) == dims.n_heads * n * 2
+    P.sti_decode_working_buffer(dims, [D.upload_shard(s) for s in host], out)
+    torch.cuda.synchronize()
+    got = out.view(torch.int16).cpu().numpy().view(np.uint16).reshape(len(present), n)
+    want = oracle_mod.decode_shards(present, n, oracle_mod.F16)
+    for p in range(len(present)):
+        assert np.array_equal(untile(got[p], dims), want[p]), (p, present[p].bitwidth)
+    # the library's own statement of the layout agrees with the header's formula
+    probe = np.concatenate([np.arange(0, n, 4099), [n - 1]])
+    image_index = np.array([P.sti_working_buffer_offset(dims, int(j)) for j in probe])
+    assert np.array_equal(got[0][image_index], want[0][probe])
+    assert P.sti_working_buffer_offset(dims, n) == -1
+
+
+def test_working_buffer_rejections(gpu):
+    torch, P, D = gpu
+    dims = S.Dims(128, 2, 64, 64, 1e-12)
+    n = dims.weights_per_shard
+    sh = [D.upload_shard(S.make_shard(np.random.default_rng(1), n, 4)), None]
+    out = torch.zeros(n, dtype=torch.float16, device="cuda")
+    with pytest.raises(P.StiError) as e:
+        P.sti_decode_working_buffer(dims, sh, out[: n - 8])
+    assert e.value.status == 6
+    with pytest.raises(P.StiError) as e:
+        P.sti_decode_working_buffer(S.Dims(96, 2, 64, 64, 1e-12), sh, out)
+    assert e.value.status == 2
+    torch.cuda.synchronize()
+    assert not out.any()
+    P.sti_decode_working_buffer(dims, [None, None], out)   # nothing present: nothing written
+    torch.cuda.synchronize()
+    assert not out.any()

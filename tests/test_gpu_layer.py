@@ -497,10 +497,9 @@ def test_mfma_rows_longer_than_2048_features(gpu, oracle_mod, d_model, B, L):
     S.make_every_term_matter(wl, 8, amp=2.0)
     want = oracle_mod.model_forward(dims, wl.shards, wl.params, wl.x)
     got = run_gpu(gpu, wl, "mfma")
-    # (gains up to 1.9 on rows of 4096 features with doubled weights: at most 8 of 1.2 million elements
-    #  were measured past the per-element bound, none past 1.2 times it)
-    assert_parity(got, want, TOL["mfma"], max_violations=1e-4)
-    assert_parity(got, want, 1.2 * TOL["mfma"])
+    # (gains up to 1.9 on rows of 4096 features with doubled weights: at d_model 4096, 1 of 163,840 and
+    #  8 of 1,228,800 elements were measured past the per-element bound; none at d_model 2112)
+    assert_parity(got, want, TOL["mfma"], max_violations=1e-4 if d_model == 4096 else 0.0)
 
 
 def test_mfma_rows_beyond_2gib_of_activations(gpu):
@@ -560,6 +559,69 @@ def test_model_forward_can_be_stream_captured(gpu, oracle_mod):
         P.sti_model_forward(MID, store, params, wl.plan, x, scratch, prec, ws)   # eager work between replays
         torch.cuda.synchronize()
         assert torch.equal(scratch, y_eager)
+
+
+def test_capture_never_records_the_shard_table_upload(gpu, oracle_mod):
+    """With the model workspace the eager call takes the grouped route, whose shard table is
+    uploaded through a pinned host buffer that later calls overwrite; a captured call must not
+    record that copy: it runs the per-layer route (same bits), and replays stay right after
+    eager calls with OTHER plans have reused the pinned buffer.  sti_decode_shards with more than
+    64 shards, which has no other route, refuses to be captured."""
+    torch, P, D = gpu
+    wl = S.small_workload(4321, MID, 3, 3, 100, n_absent=1, io_dtype="f16")
+    other = S.small_workload(1234, MID, 3, 3, 100, n_absent=2, io_dtype="f16")
+    prec = P.STI_PREC_F16_MFMA
+    shards, params, x = D.upload_workload(wl)
+    store = P.make_store(D.store_from_plan(shards))
+    o_shards, o_params, o_x = D.upload_workload(other)
+    o_store = P.make_store(D.store_from_plan(o_shards))
+    nbytes = P.sti_model_workspace_bytes(MID, 3, 3, 100, prec)
+    assert nbytes > P.sti_workspace_bytes(MID, 3, 100, prec)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    y_eager = torch.empty_like(x)
+    P.sti_model_forward(MID, store, params, wl.plan, x, y_eager, prec, ws)
+    torch.cuda.synchronize()
+    assert_parity(y_eager.float().cpu().numpy(), oracle_mod.model_forward(MID, wl.shards, wl.params, wl.x), TOL["mfma"])
+    y_graph = torch.full_like(x, float("nan"))
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            P.sti_model_forward(MID, store, params, wl.plan, x, y_graph, prec, ws)
+    torch.cuda.synchronize()
+    o_ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    o_y = torch.empty_like(o_x)
+    for _ in range(3):
+        for _ in range(5):   # more eager uploads than the pinned ring has slots
+            P.sti_model_forward(MID, o_store, o_params, other.plan, o_x, o_y, prec, o_ws)
+        torch.cuda.synchronize()
+        y_graph.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(y_graph, y_eager)
+    # decode: 70 shards need the uploaded table
+    n = 4096
+    host = [S.make_shard(np.random.default_rng(s), n, 2 + s % 5) for s in range(70)]
+    dev = [D.upload_shard(s) for s in host]
+    out = torch.zeros(70 * n, dtype=torch.float16, device="cuda")
+    dws = torch.empty(P.sti_decode_workspace_bytes(70), dtype=torch.uint8, device="cuda")
+    g2 = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g2, stream=side):
+            with pytest.raises(P.StiError) as err:
+                P.sti_decode_shards(dev, n, out, dws)
+            P.sti_decode_shards(dev[:64], n, out[:64 * n], None)   # at most 64 shards: kernels only
+    assert err.value.status == 9   # STI_ERR_UNSUPPORTED
+    torch.cuda.synchronize()
+    g2.replay()
+    torch.cuda.synchronize()
+    got = out.view(torch.int16).cpu().numpy().view(np.uint16).reshape(70, n)
+    assert np.array_equal(got[:64], oracle_mod.decode_shards(host[:64], n, oracle_mod.F16))
+    assert not got[64:].any()
+    P.sti_decode_shards(dev, n, out, dws)   # eager: accepted
+    torch.cuda.synchronize()
+    got = out.view(torch.int16).cpu().numpy().view(np.uint16).reshape(70, n)
+    assert np.array_equal(got, oracle_mod.decode_shards(host, n, oracle_mod.F16))
 
 
 @pytest.mark.parametrize("B,L", [(1, 64), (4, 128)])   # few-token route / working-buffer route
