@@ -182,6 +182,33 @@ sti_status sti_layer_forward(const sti_dims *dims, const sti_shard *shards,
                              void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /* ---------------------------------------------------------------------------
+ * sti_layer_forward for callers that cannot allocate device memory (code under graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): the same layer, the
+ * same kernels and the same results, with the workspace taken from an array that is
+ * part of the library's device image instead of from the caller.  The call allocates
+ * nothing (no device, pinned or pageable memory) and enqueues kernel launches only.
+ *
+ * The array holds sti_static_scratch_bytes() = 64 MiB on every GPU the library runs on,
+ * from the first use of the library on that GPU until the process ends.  A call whose
+ * sti_workspace_bytes(dims, batch, seq, precision) exceeds it returns STI_ERR_WORKSPACE
+ * before anything is enqueued (BERT-base dimensions fit 20 x 128 tokens with
+ * STI_PREC_F16_MFMA and 8 x 128 with STI_PREC_F32; d_model 1024 with 16 shards fits
+ * 12 x 128 and 2 x 128).  All calls on one GPU share the one array:
+ * calls whose kernels may overlap on that GPU (different streams, or several host
+ * threads) race; calls on one stream are ordered and safe.  The array keeps the last
+ * call's contents; no kernel of the layer reads scratch memory it has not written in
+ * the same call, so nothing needs clearing.  The array's address on the current device is
+ * looked up on the first call there, which should be made outside stream capture.
+ * Other arguments and errors as for sti_layer_forward.
+ * ------------------------------------------------------------------------- */
+size_t sti_static_scratch_bytes(void);
+
+sti_status sti_layer_forward_static(const sti_dims *dims, const sti_shard *shards,
+                                    const sti_layer_params *params, const void *x, void *y,
+                                    sti_dtype io_dtype, int batch, int seq, sti_precision precision,
+                                    void *hip_stream);
+
+/* ---------------------------------------------------------------------------
  * The working buffer of the matrix-core path by itself (Section "Submodel execution":
  * all selected shards of a layer are decompressed into a working buffer before the
  * layer's computation starts).  sti_decode_working_buffer writes what sti_layer_forward

@@ -96,6 +96,12 @@ def _load():
         C.POINTER(StiDims), C.c_int, C.POINTER(StiShard), C.POINTER(StiLayerParams),
         C.POINTER(C.c_int8), C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int,
         C.c_void_p, C.c_size_t, C.c_void_p]
+    L.sti_static_scratch_bytes.restype = C.c_size_t
+    L.sti_static_scratch_bytes.argtypes = []
+    L.sti_layer_forward_static.restype = C.c_int
+    L.sti_layer_forward_static.argtypes = [
+        C.POINTER(StiDims), C.POINTER(StiShard), C.POINTER(StiLayerParams), C.c_void_p,
+        C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p]
     L.sti_working_buffer_bytes.restype = C.c_size_t
     L.sti_working_buffer_bytes.argtypes = [C.POINTER(StiDims)]
     L.sti_working_buffer_offset.restype = C.c_int64
@@ -271,6 +277,17 @@ def sti_layer_forward(dims, shards: Sequence, params, x, y, precision: int, work
                                _stream_handle(stream))
     if st != 0:
         raise StiError(st, "sti_layer_forward")
+
+
+def sti_layer_forward_static(dims, shards: Sequence, params, x, y, precision: int, stream=None) -> None:
+    """sti_layer_forward with the library's own fixed scratch array as workspace (no allocation)."""
+    d = make_dims(dims)
+    arr = shard_array(shards)
+    p = make_params(params)
+    st = lib.sti_layer_forward_static(C.byref(d), arr, C.byref(p), _ptr(x), _ptr(y), _dtype_code(x),
+                                      int(x.shape[0]), int(x.shape[1]), int(precision), _stream_handle(stream))
+    if st != 0:
+        raise StiError(st, "sti_layer_forward_static")
 
 
 def sti_layer_forward_masked(dims, shards: Sequence, params, x, y, key_lengths, precision: int,

@@ -466,6 +466,35 @@ using namespace sti;
 
 namespace {
 
+// Scratch memory of sti_layer_forward_static: what sti_layer_forward takes as `workspace`
+// (working buffer, projections' outputs, partial sums), for callers that cannot allocate.
+// One copy per GPU, at an address of its own on each, held until the process ends.
+constexpr size_t kStaticScratchBytes = (size_t)64 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+// Device address of `scratch` on the current device, looked up once per device (in host code
+// the array's name is only a handle for this lookup, never an address a kernel may use).
+hipError_t static_scratch(uint8_t **out)
+{
+    constexpr int kMaxDevices = 64;
+    static std::mutex mu;
+    static uint8_t *per_device[kMaxDevices] = {};
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!per_device[dev]) {
+        void *ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!ptr) return hipErrorInvalidSymbol;
+        per_device[dev] = (uint8_t *)ptr;
+    }
+    *out = per_device[dev];
+    return hipSuccess;
+}
+
 // masked: the call came through a *_masked entry point and key_lengths must be usable
 sti_status layer_forward(const sti_dims *dims, const sti_shard *shards,
                          const sti_layer_params *params, const void *x, void *y,
@@ -672,6 +701,24 @@ sti_status sti_layer_forward(const sti_dims *dims, const sti_shard *shards,
     return layer_forward(dims, shards, params, x, y, io_dtype, batch, seq, false, nullptr, precision,
                          workspace, workspace_bytes, hip_stream);
 }
+
+sti_status sti_layer_forward_static(const sti_dims *dims, const sti_shard *shards,
+                                    const sti_layer_params *params, const void *x, void *y,
+                                    sti_dtype io_dtype, int batch, int seq, sti_precision precision,
+                                    void *hip_stream)
+{
+    // everything that can be refused is refused before the scratch array is looked at
+    sti_status st = check_dims(dims, batch, seq, precision);
+    if (st != STI_OK) return st;
+    const size_t need = workspace_layout(*dims, (int64_t)batch * seq, precision).total;
+    if (need > kStaticScratchBytes) return STI_ERR_WORKSPACE;
+    uint8_t *scratch_ptr = nullptr;
+    if (static_scratch(&scratch_ptr) != hipSuccess) return STI_ERR_HIP;
+    return layer_forward(dims, shards, params, x, y, io_dtype, batch, seq, false, nullptr, precision,
+                         scratch_ptr, kStaticScratchBytes, hip_stream);
+}
+
+size_t sti_static_scratch_bytes(void) { return kStaticScratchBytes; }
 
 sti_status sti_layer_forward_masked(const sti_dims *dims, const sti_shard *shards,
                                     const sti_layer_params *params, const void *x, void *y,
