@@ -2,7 +2,7 @@
 
 Argument marshalling only: every step of the path runs in the HIP kernels of
 ``libsti.so``.  Importing this package fails loudly when the library has not
-been built (``python -m paper_2207_05022_amd.build``); there is no fallback.
+been built (``python paper_2207_05022_amd/build.py``); there is no fallback.
 """
 from .binding import (  # noqa: F401
     STI_F32, STI_F16, STI_BF16, STI_PREC_F32, STI_PREC_F16_MFMA,

@@ -67,7 +67,7 @@ def _load():
     if not os.path.exists(LIB_PATH):
         raise ImportError(
             f"{LIB_PATH} is missing: build the HIP library first "
-            "(python -m paper_2207_05022_amd.build); there is no CPU fallback")
+            "(python paper_2207_05022_amd/build.py); there is no CPU fallback")
     L = C.CDLL(LIB_PATH)
     L.sti_status_string.restype = C.c_char_p
     L.sti_status_string.argtypes = [C.c_int]
