@@ -2,10 +2,13 @@
 """Throughput of the shard-decode + encoder-layer path on one MI355X.
 
 One step = one pass of the whole path over one batch: a 12-layer mixed-bitwidth
-BERT-base forward (decode fused into the projections, attention, LayerNorms)
-over 32 x 128 tokens.  The same run also times the standalone shard-decode
-entry point on the 1 GiB packed stream and the CPU oracle on a bounded sample.
-Prints ONE JSON line.
+BERT-base forward over 32 x 128 tokens (per group of layers: shards decompressed
+into the binary16 working buffer; per layer: four projections on the matrix
+cores, attention, two LayerNorms).  The same run also times the standalone
+shard-decode entry point on the 1 GiB packed stream, the three single-sequence
+configurations (where the projections decode the packed streams in their weight
+loader) and the CPU oracle on a bounded sample, and compares the outputs of the
+timed calls with the oracle's.  Prints ONE JSON line.
 """
 from __future__ import annotations
 
@@ -196,10 +199,35 @@ def bench_host_link(P, D, torch, S, steps, warmup):
     return out
 
 
-def bench_few_token(P, D, torch, S, steps, warmup):
+def parity(got, want, tol):
+    """max |y - y_ref| / max |y_ref|, and the fraction of elements with
+    |y - y_ref| > tol * |y_ref| + tol * rms(y_ref) (expected 0)."""
+    got = np.asarray(got, dtype=np.float64)
+    delta = np.abs(got - want)
+    rms = float(np.sqrt(np.mean(want * want)))
+    bad = (delta > tol * np.abs(want) + tol * rms) | ~np.isfinite(got)
+    return {"max_rel_err": float(np.max(delta) / np.max(np.abs(want))), "tolerance": tol,
+            "elementwise_violations": float(np.mean(bad))}
+
+
+def packed_bytes(wl):
+    """Bytes of the selected shard versions (index streams or float32 weights) and their codebooks."""
+    total = 0
+    for row in wl.shards:
+        for s in row:
+            if s is not None:
+                total += s.data.nbytes + (0 if s.codebook is None else s.codebook.nbytes)
+    return total
+
+
+def bench_few_token(P, D, torch, S, steps, warmup, with_oracle):
     """Configurations 0, 2 and 3 (one sequence of 128 / 128 / 256 tokens): the latency-bound
-    regime of single-input inference.  Resident shards, float32 in and out."""
-    out = {}
+    regime of single-input inference (Section "Submodel execution": one input at a time).
+    Resident shards, float32 in and out.  Fractions are of the matrix-core and HBM peaks for the
+    algorithmic flops and bytes (selected shards as stored + input + output); a forward is a chain
+    of dependent launches of a few microseconds each, so both are small by construction."""
+    out = {"regime": "latency-bound: 8 dependent launches per layer; fractions of both rooflines are "
+                     "reported for completeness"}
     prec = P.STI_PREC_F16_MFMA
     for name, make in (("config0", S.config0), ("config2", S.config2), ("config3", S.config3)):
         wl = make()
@@ -217,9 +245,19 @@ def bench_few_token(P, D, torch, S, steps, warmup):
             run()
         torch.cuda.synchronize()
         ms = (time.perf_counter() - t0) / steps * 1e3
+        flops = sum(layer_flops_per_token(wl.dims, wl.seq, int((wl.plan[l] != 0).sum()))
+                    for l in range(wl.n_layers)) * wl.tokens
+        nbytes = packed_bytes(wl) + 2 * x.numel() * x.element_size()
         out[name] = {"tokens": wl.tokens, "layers": wl.n_layers, "ms_per_forward": round(ms, 4),
                      "us_per_layer": round(ms * 1e3 / wl.n_layers, 2),
-                     "tokens_per_s": round(wl.tokens / ms * 1e3, 1)}
+                     "tokens_per_s": round(wl.tokens / ms * 1e3, 1),
+                     "algorithmic_gflop": round(flops / 1e9, 3), "algorithmic_mbytes": round(nbytes / 1e6, 2),
+                     "frac_mfma_peak": round(flops / (ms * 1e-3) / 1e12 / MFMA_F16_PEAK_TFLOPS, 5),
+                     "frac_hbm_peak": round(nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 5)}
+        if with_oracle:
+            import oracle
+            want = oracle.model_forward(wl.dims, wl.shards, wl.params, wl.x)
+            out[name]["parity"] = parity(y.float().cpu().numpy(), want, 2e-2)
     return out
 
 
@@ -252,16 +290,19 @@ def bench_quantizer(P, torch, S, steps, warmup):
     return out
 
 
-def cpu_baselines(S, wl, ds):
-    """The oracle as it stands, on a bounded sample of both workloads."""
+def cpu_baselines(S, wl, y, ds):
+    """The oracle as it stands, on a bounded sample of both workloads; its output for the model
+    workload is also what the output `y` of the timed calls is compared with."""
     import oracle
     threads = oracle.num_threads()
     nseq = wl.batch          # the whole batch: about 10-15 s on 16 host threads
     t0 = time.perf_counter()
-    oracle.model_forward(wl.dims, wl.shards, wl.params, wl.x[:nseq])
+    want = oracle.model_forward(wl.dims, wl.shards, wl.params, wl.x[:nseq])
     dt = time.perf_counter() - t0
     model = {"value": round(nseq * wl.seq / dt, 2), "unit": "tokens/s", "cores": threads, "kind": "oracle",
              "sample": f"{nseq} of {wl.batch} sequences through all {wl.n_layers} layers ({dt:.1f} s)"}
+    model_parity = parity(y.float().cpu().numpy()[:nseq], want, 2e-2)
+    model_parity["compared"] = f"output of the timed sti_model_forward calls, {nseq} of {wl.batch} sequences"
     # decode: a few shards of every bitwidth
     pick = [ds.shard(i) for i in range(ds.n_shards)]   # the whole stream: a few seconds
     t0 = time.perf_counter()
@@ -270,7 +311,7 @@ def cpu_baselines(S, wl, ds):
     nbytes = sum(s.data.nbytes for s in pick) + out.nbytes
     dec = {"value": round(nbytes / dt / 1e9, 3), "unit": "GB/s", "cores": threads, "kind": "oracle",
            "sample": f"{len(pick)} of {ds.n_shards} shards, {dt:.1f} s"}
-    return model, dec
+    return model, dec, model_parity
 
 
 def main():
@@ -286,8 +327,8 @@ def main():
     ap.add_argument("--host-link", action="store_true",
                     help="also time the load || compute pipeline with the shard streams in pinned host "
                          "memory (reported beside the headline value, never as it)")
-    ap.add_argument("--few-token", action="store_true",
-                    help="also time configurations 0, 2 and 3 (reported beside the headline value)")
+    ap.add_argument("--no-few-token", action="store_true",
+                    help="leave out configurations 0, 2 and 3 (reported beside the headline value)")
     ap.add_argument("--quantize", action="store_true",
                     help="also time the outlier-aware quantizer on one BERT-base layer")
     args = ap.parse_args()
@@ -313,7 +354,7 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
-    model, (wl, _) = bench_model(P, D, torch, S, args.steps, args.warmup)
+    model, (wl, y) = bench_model(P, D, torch, S, args.steps, args.warmup)
     decode, ds = bench_decode(P, torch, S, args.steps, args.warmup)
     line = {
         "metric": METRIC, "value": round(model["tokens_per_s"], 1), "unit": "tokens/s",
@@ -330,13 +371,14 @@ def main():
     }
     if args.host_link:
         line["host_link_pipeline"] = bench_host_link(P, D, torch, S, args.steps, args.warmup)
-    if args.few_token:
-        line["few_token"] = bench_few_token(P, D, torch, S, args.steps, args.warmup)
+    if not args.no_few_token:
+        line["few_token"] = bench_few_token(P, D, torch, S, args.steps, args.warmup, not args.no_cpu_baseline)
     if args.quantize:
         line["quantizer"] = bench_quantizer(P, torch, S, args.steps, args.warmup)
     if not args.no_cpu_baseline:
-        cpu_model, cpu_dec = cpu_baselines(S, wl, ds)
+        cpu_model, cpu_dec, model_parity = cpu_baselines(S, wl, y, ds)
         line["cpu_baseline"] = cpu_model
+        line["parity"] = model_parity
         line["decode"]["cpu_baseline"] = cpu_dec
     print(json.dumps(line))
 
