@@ -290,6 +290,65 @@ def bench_quantizer(P, torch, S, steps, warmup):
     return out
 
 
+def bench_ceilings(torch, steps):
+    """What the chip delivers for the two resources this path is bound by, measured with kernels that
+    use nothing else (libsti_probes.so), and what the vendor's GEMM library reaches on the four
+    projection shapes of configuration 4 (torch.nn.functional.linear on binary16 operands: a plain
+    GEMM + bias without GELU or residual; a reference point, not part of the path)."""
+    import ctypes as C
+    lib = C.CDLL(os.path.join(ROOT, "paper_2207_05022_amd", "libsti_probes.so"))
+    lib.sti_probe_mfma.argtypes = [C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p,
+                                   C.POINTER(C.c_double), C.POINTER(C.c_double)]
+    lib.sti_probe_stream.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64, C.c_int, C.c_int, C.c_void_p,
+                                     C.POINTER(C.c_double), C.POINTER(C.c_double)]
+    stream = C.c_void_p(torch.cuda.current_stream().cuda_stream)
+    out = {}
+    scratch = torch.empty(256 * 768, dtype=torch.float32, device="cuda")
+    ms, work = C.c_double(), C.c_double()
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    for waves in (4, 12):
+        rc = lib.sti_probe_mfma(cus, waves, 3000, 5, scratch.data_ptr(), stream, C.byref(ms), C.byref(work))
+        assert rc == 0, rc
+        tflops = work.value / (ms.value * 1e-3) / 1e12
+        out[f"mfma_only_loop_{waves}_waves_per_cu"] = {
+            "TFLOP/s": round(tflops, 1), "frac_of_published_peak": round(tflops / MFMA_F16_PEAK_TFLOPS, 4),
+            "implied_clock_GHz": round(tflops * 1e12 / (cus * 4096.0) / 1e9, 3), "ms_per_launch": round(ms.value, 4)}
+    n_in = 1 << 26
+    src = torch.empty(n_in * 16, dtype=torch.uint8, device="cuda").random_(0, 256)
+    dst = torch.empty(n_in * 16 * 5, dtype=torch.uint8, device="cuda")
+    for ratio in (1, 4, 5):
+        rc = lib.sti_probe_stream(src.data_ptr(), dst.data_ptr(), n_in, ratio, 5, stream, C.byref(ms), C.byref(work))
+        assert rc == 0, rc
+        gbs = work.value / (ms.value * 1e-3) / 1e9
+        out[f"hbm_stream_read_to_write_1_to_{ratio}"] = {"GB/s": round(gbs, 1), "frac_of_published_peak": round(gbs / HBM_PEAK_GBS, 4),
+                                                        "bytes_per_launch": int(work.value), "ms_per_launch": round(ms.value, 4)}
+    del src, dst
+    vendor = {}
+    for name, (M, N, K) in (("gemm_qkv", (4096, 2304, 768)), ("gemm_out", (4096, 768, 768)),
+                            ("gemm_ffn_up", (4096, 3072, 768)), ("gemm_ffn_down", (4096, 768, 3072))):
+        a = torch.randn(M, K, device="cuda", dtype=torch.float16)
+        w = torch.randn(N, K, device="cuda", dtype=torch.float16) * 0.02
+        b = torch.randn(N, device="cuda", dtype=torch.float16)
+        for _ in range(5):
+            torch.nn.functional.linear(a, w, b)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        reps = max(20, steps * 5)
+        e0.record()
+        for _ in range(reps):
+            torch.nn.functional.linear(a, w, b)
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) / reps * 1e3
+        vendor[name] = {"us_per_call": round(us, 2), "TFLOP/s": round(2.0 * M * N * K / us / 1e6, 1),
+                        "frac_of_published_peak": round(2.0 * M * N * K / us / 1e6 / MFMA_F16_PEAK_TFLOPS, 4)}
+    flops = sum(2.0 * 4096 * n * k for n, k in ((2304, 768), (768, 768), (3072, 768), (768, 3072)))
+    us = sum(v["us_per_call"] for v in vendor.values())
+    vendor["mean_of_the_four"] = {"us_per_call": round(us / 4, 2), "TFLOP/s": round(flops / us / 1e6, 1),
+                                  "frac_of_published_peak": round(flops / us / 1e6 / MFMA_F16_PEAK_TFLOPS, 4)}
+    out["vendor_gemm_library_same_shapes"] = vendor
+    return out
+
+
 def cpu_baselines(S, wl, y, ds):
     """The oracle as it stands, on a bounded sample of both workloads; its output for the model
     workload is also what the output `y` of the timed calls is compared with."""
@@ -329,6 +388,9 @@ def main():
                          "memory (reported beside the headline value, never as it)")
     ap.add_argument("--no-few-token", action="store_true",
                     help="leave out configurations 0, 2 and 3 (reported beside the headline value)")
+    ap.add_argument("--ceilings", action="store_true",
+                    help="also run the ceiling probes: an MFMA-only loop, HBM streams with the read : write mix of "
+                         "decompression, and the vendor GEMM library on configuration 4's projection shapes")
     ap.add_argument("--quantize", action="store_true",
                     help="also time the outlier-aware quantizer on one BERT-base layer")
     args = ap.parse_args()
@@ -373,6 +435,8 @@ def main():
         line["host_link_pipeline"] = bench_host_link(P, D, torch, S, args.steps, args.warmup)
     if not args.no_few_token:
         line["few_token"] = bench_few_token(P, D, torch, S, args.steps, args.warmup, not args.no_cpu_baseline)
+    if args.ceilings:
+        line["ceilings"] = bench_ceilings(torch, args.steps)
     if args.quantize:
         line["quantizer"] = bench_quantizer(P, torch, S, args.steps, args.warmup)
     if not args.no_cpu_baseline:

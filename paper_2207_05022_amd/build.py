@@ -11,6 +11,8 @@ CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 OBJ_DIR = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libsti.so")
+PROBES_SRC = os.path.join(CSRC, "probes", "ceilings.hip")
+PROBES_LIB = os.path.join(HERE, "libsti_probes.so")   # ceiling probes for bench.py --ceilings, not part of libsti
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
@@ -40,10 +42,12 @@ def build(verbose: bool = False) -> str:
             objs = list(pool.map(_compile, srcs))
         subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs],
                        check=True, stderr=subprocess.PIPE, text=True)
+        subprocess.run([HIPCC, *FLAGS, "-shared", PROBES_SRC, "-o", PROBES_LIB],
+                       check=True, stderr=subprocess.PIPE, text=True)
     except subprocess.CalledProcessError as err:
         raise RuntimeError(f"hipcc failed: {' '.join(err.cmd)}\n{err.stderr}") from None
     if verbose:
-        print(f"built {LIB} from {len(srcs)} sources")
+        print(f"built {LIB} from {len(srcs)} sources and {PROBES_LIB}")
     return LIB
 
 
