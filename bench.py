@@ -106,6 +106,9 @@ def bench_model(P, D, torch, S, steps, warmup):
     gemm_launches = sum(prof[k][0] for k in gemm_kinds)
     gemm_ms = sum(prof[k][1] for k in gemm_kinds)
     flops_per_forward_gemm = sum(gemm_flops(dims, wl.tokens, present_total, k) for k in gemm_kinds)
+    attention_inside = prof["attention"][0] == 0   # the Q/K/V launches ran the attention as well
+    if attention_inside:
+        flops_per_forward_gemm += 4.0 * wl.seq * dims.d_head * present_total * wl.tokens
     launches_per_forward = gemm_launches / steps
     flops_per_launch = flops_per_forward_gemm / launches_per_forward
     avg_launch_ms = gemm_ms / gemm_launches
@@ -117,7 +120,9 @@ def bench_model(P, D, torch, S, steps, warmup):
         "ms_per_step": ms_per_step,
         "whole_path_tflops": total_flops / (ms_per_step * 1e-3) / 1e12,
         "roofline": {
-            "bound": "mfma", "kernel": "gemm_wide_kernel (QKV, O, FFN1, FFN2 projections; weights from the binary16 working buffer)",
+            "bound": "mfma",
+            "kernel": "gemm_wide_kernel (Q/K/V projection" + (" with the two heads' attention" if attention_inside else "")
+                      + ", O, FFN1 + GELU, FFN2 projections; weights from the binary16 working buffer)",
             "achieved": round(achieved_tflops, 2), "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s",
             "frac": round(achieved_tflops / MFMA_F16_PEAK_TFLOPS, 4), "traffic": measured_traffic("gemm"),
             "avg_launch_us": round(avg_launch_ms * 1e3, 2), "launches_per_step": launches_per_forward,

@@ -379,8 +379,8 @@ sti_status run_layer(const sti_dims &d, const sti_shard *shards, const sti_layer
     const int64_t partial_stride = (int64_t)T * dm;
     int pre_partials = 1;   // partial sums the last K-split GEMM left in `pre`
     auto gemm = [&](const GemmProblem &p, const GemmBlocks &blk) {
-        static const int cls[4] = {STI_K_GEMM_QKV, STI_K_GEMM_FFN_UP, STI_K_GEMM_OUT,
-                                   STI_K_GEMM_FFN_DOWN};
+        static const int cls[5] = {STI_K_GEMM_QKV, STI_K_GEMM_FFN_UP, STI_K_GEMM_OUT,
+                                   STI_K_GEMM_FFN_DOWN, STI_K_GEMM_QKV};
         return timed(cls[p.kind], stream, [&] {
             if (f32) return launch_gemm_f32(p, blk, stream);
             if (!skinny) {
@@ -414,11 +414,18 @@ sti_status run_layer(const sti_dims &d, const sti_shard *shards, const sti_layer
         p.kind = GEMM_QKV; p.T = T; p.n_blocks = m; p.block_rows = 3 * dh; p.block_cols = dm;
         p.d_head = dh; p.A = in; p.lda = dm; p.C = qkv; p.ldc = m * 3 * dh;
         p.bias0 = prm.bq; p.bias1 = prm.bk; p.bias2 = prm.bv;
-        STI_TRY(gemm(p, bq));
-        STI_TRY(timed(STI_K_ATTENTION, stream, [&] {
-            return f32 ? launch_attention_f32((const float *)qkv, (float *)ctx, B, Lseq, m, dh, key_lengths, stream)
-                       : launch_attention_mfma(qkv, ctx, B, Lseq, m, dh, key_lengths, stream);
-        }));
+        if (!f32 && !skinny && gemm_wide_fuses_attention(B, Lseq, m, dh)) {
+            // sequences of 128 tokens: the projection's 128-row tiles are whole sequences, and its
+            // workgroups go on to the attention of the heads they hold (no Q/K/V buffer)
+            p.kind = GEMM_QKV_ATTN; p.C = ctx; p.ldc = m * dh; p.key_lengths = key_lengths;
+            STI_TRY(gemm(p, bq));
+        } else {
+            STI_TRY(gemm(p, bq));
+            STI_TRY(timed(STI_K_ATTENTION, stream, [&] {
+                return f32 ? launch_attention_f32((const float *)qkv, (float *)ctx, B, Lseq, m, dh, key_lengths, stream)
+                           : launch_attention_mfma(qkv, ctx, B, Lseq, m, dh, key_lengths, stream);
+            }));
+        }
     }
     memset(&p, 0, sizeof(p));
     p.kind = GEMM_OUT; p.T = T; p.n_blocks = m; p.block_rows = dm; p.block_cols = dh; p.d_head = dh;

@@ -20,6 +20,11 @@
 //     output columns of one token row; v_permlane32_swap merges them into 16-byte pieces,
 //     which get bias / GELU / residual in registers and leave through an LDS copy of the
 //     whole tile, so that every global store instruction writes whole rows of the tile.
+//
+// Sequences of exactly 128 tokens (the padded length the paper profiles with): a 128-row tile is
+// one whole sequence, so the Q/K/V projection is cut into 128 x 384 tiles = Q | K | V of two
+// heads, and the workgroup that has multiplied such a tile keeps it in LDS and computes those
+// heads' attention itself (kind GEMM_QKV_ATTN): no Q/K/V buffer in memory and no attention launch.
 #include "sti_internal.hpp"
 #include "weight_loader.hpp"
 
@@ -30,6 +35,7 @@ constexpr int BK = 64;   // K positions per LDS stage
 constexpr int kGroupRows = 8;   // row tiles per band of the tile order ...
 constexpr int kRowMajorColumnTiles = 12;   // ... used beyond this many column tiles
 
+typedef _Float16 half4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(1))) const void global_cptr;
 typedef __attribute__((address_space(3))) void lds_ptr;
 
@@ -57,6 +63,12 @@ __device__ inline float gelu_erf(float z)
     return z * fmaf(zc, r, 0.5f);
 }
 
+// LDS of the attention that follows the Q/K/V tile (GEMM_QKV_ATTN): per head Q and K row-major
+// with padded rows and V transposed, for 128 positions of 64 features
+constexpr int ATT_L = 128, ATT_DH = 64, ATT_KPAD = ATT_DH + 8, ATT_VTS = ATT_L + 8;
+constexpr int ATT_HEAD_HALVES = 2 * ATT_L * ATT_KPAD + ATT_DH * ATT_VTS;
+constexpr size_t kAttentionLdsBytes = (size_t)2 * ATT_HEAD_HALVES * 2;
+
 template <int RA, int NW, int KS>
 constexpr size_t wide_lds_bytes()
 {
@@ -75,7 +87,9 @@ template <int KIND, int RA, int NW, int KS, bool EARLY>
 __global__ __launch_bounds__(NW * KS * 64, 3) void gemm_wide_kernel(GemmProblem p, GemmBlocks blocks)
 {
     constexpr int BM = RA * 32, BN = NW * 32, NT = NW * KS * 64, NTH = NW * 64;
-    constexpr bool n_split = (KIND == GEMM_QKV || KIND == GEMM_FFN_UP);
+    constexpr bool n_split = (KIND == GEMM_QKV || KIND == GEMM_FFN_UP || KIND == GEMM_QKV_ATTN);
+    constexpr bool qkv = (KIND == GEMM_QKV || KIND == GEMM_QKV_ATTN);
+    static_assert(KIND != GEMM_QKV_ATTN || (RA == 4 && NW == 12 && KS == 1), "two heads of one 128-token sequence per tile");
     constexpr int STAGE = BM * BK;              // halves per A stage
     constexpr int FETCHES = BM / 8;             // fetch instructions per A stage: 8 rows (1 KiB) each
     constexpr int FPW = (FETCHES + NW - 1) / NW;   // per wave: wave w issues fetches w, w + NW, ...
@@ -211,7 +225,7 @@ __global__ __launch_bounds__(NW * KS * 64, 3) void gemm_wide_kernel(GemmProblem 
         for (int q = 0; q < 2; ++q) {
             const int c = 16 * q + 8 * g;     // first column of the piece inside the wave's strip
             const float *bp;
-            if constexpr (KIND == GEMM_QKV) {
+            if constexpr (qkv) {
                 const int nrow = nrow0 + c;
                 const int which = nrow / p.d_head, e0 = nrow - which * p.d_head;
                 bp = (which == 0 ? p.bias0 : (which == 1 ? p.bias1 : p.bias2)) + blocks.b[nblk].shard * p.d_head + e0;
@@ -297,6 +311,123 @@ __global__ __launch_bounds__(NW * KS * 64, 3) void gemm_wide_kernel(GemmProblem 
     //  made those launches 2 % slower, measured twice)
     if (!PRE) load_epilogue_operands();
     __syncthreads();   // every wave is done with the A stages
+    if constexpr (KIND == GEMM_QKV_ATTN) {
+        // ---- the tile is Q | K | V of heads 2 tile_n and 2 tile_n + 1 for the 128 positions of
+        //      sequence tile_m: leave them in LDS (binary16, bias added: the values the unfused
+        //      route stores) and run the two heads' attention (Section "A primer on transformer":
+        //      per-head attention scores) with eight of the twelve waves, 32 queries each ----
+        _Float16 *hb = (_Float16 *)smem_raw + (wave / 6) * ATT_HEAD_HALVES;   // this wave's head
+        const int part = (wave % 6) >> 1;      // 0 Q, 1 K, 2 V (wave-uniform)
+        const int ch = (wave & 1) * 32;        // first feature of the wave's 32 columns
+#pragma unroll
+        for (int i = 0; i < RA; ++i) {
+            const int row = i * 32 + lr;
+#pragma unroll
+            for (int q = 0; q < 2; ++q) {
+                half8 o;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float lo = acc[i][(2 * q) * 4 + e], hi = acc[i][(2 * q + 1) * 4 + e];
+                    const auto sw = __builtin_amdgcn_permlane32_swap(__builtin_bit_cast(uint32_t, lo),
+                                                                     __builtin_bit_cast(uint32_t, hi), false, false);
+                    const uint32_t s0 = sw[0], s1 = sw[1];
+                    o[e] = (_Float16)(__builtin_bit_cast(float, s0) + bias[q][0][e]);
+                    o[4 + e] = (_Float16)(__builtin_bit_cast(float, s1) + bias[q][1][e]);
+                }
+                const int c = ch + 16 * q + 8 * g;
+                if (part < 2) {
+                    *(half8 *)(hb + part * (ATT_L * ATT_KPAD) + row * ATT_KPAD + c) = o;
+                } else {
+                    _Float16 *vt = hb + 2 * (ATT_L * ATT_KPAD);
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) vt[(c + e) * ATT_VTS + row] = o[e];
+                }
+            }
+        }
+        __syncthreads();
+        const int head = tile_n * 2 + (wave >> 2);          // present-head index of waves 0..7
+        if (wave >= 8 || head >= p.n_blocks) return;
+        hb = (_Float16 *)smem_raw + (wave >> 2) * ATT_HEAD_HALVES;
+        const _Float16 *Qs = hb, *Ks = hb + ATT_L * ATT_KPAD, *Vt = hb + 2 * (ATT_L * ATT_KPAD);
+        int Lk = ATT_L;
+        if (p.key_lengths) Lk = min(max(p.key_lengths[tile_m], 1), ATT_L);
+        const int qrow = (wave & 3) * 32 + lr;
+        half8 qf[4];
+#pragma unroll
+        for (int s = 0; s < 4; ++s) qf[s] = *(const half8 *)(Qs + qrow * ATT_KPAD + s * 16 + g * 8);
+        const float scale = 0.125f * 1.44269504088896340736f;   // 1/sqrt(64) * log2(e)
+        const int nkb = (Lk + 31) / 32;
+        float16v sc[4];
+        float mx = -INFINITY;
+#pragma unroll
+        for (int kb = 0; kb < 4; ++kb) {
+            if (kb >= nkb) break;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) sc[kb][v] = 0.f;
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                const half8 kf = *(const half8 *)(Ks + (kb * 32 + lr) * ATT_KPAD + s * 16 + g * 8);
+                sc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf, qf[s], sc[kb], 0, 0, 0);
+            }
+            if (kb * 32 + 32 > Lk) {   // keys past Lk sit in the last block only
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int key = kb * 32 + (v >> 2) * 8 + g * 4 + (v & 3);
+                    sc[kb][v] = (key < Lk) ? sc[kb][v] : -INFINITY;
+                }
+            }
+#pragma unroll
+            for (int v = 0; v < 16; ++v) mx = fmaxf(mx, sc[kb][v]);
+        }
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        const float shift = -mx * scale;
+        float run_sum = 0.f;
+        float16v ov[2];
+#pragma unroll
+        for (int e = 0; e < 2; ++e)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) ov[e][v] = 0.f;
+#pragma unroll
+        for (int kb = 0; kb < 4; ++kb) {
+            if (kb >= nkb) break;
+            uint32_t pk[8];
+#pragma unroll
+            for (int v = 0; v < 16; v += 2) {
+                const float p0 = __builtin_amdgcn_exp2f(fmaf(sc[kb][v], scale, shift));
+                const float p1 = __builtin_amdgcn_exp2f(fmaf(sc[kb][v + 1], scale, shift));
+                run_sum += p0 + p1;
+                pk[v / 2] = (uint32_t)__builtin_bit_cast(uint16_t, (_Float16)p0) |
+                            ((uint32_t)__builtin_bit_cast(uint16_t, (_Float16)p1) << 16);
+            }
+#pragma unroll
+            for (int s2 = 0; s2 < 2; ++s2) {
+                const u32x4 pv = {pk[4 * s2], pk[4 * s2 + 1], pk[4 * s2 + 2], pk[4 * s2 + 3]};
+                const half8 pf = __builtin_bit_cast(half8, pv);
+                const int key0 = kb * 32 + (2 * s2) * 8 + g * 4;
+#pragma unroll
+                for (int e = 0; e < 2; ++e) {
+                    const _Float16 *vrow = Vt + (e * 32 + lr) * ATT_VTS + key0;
+                    const u32x2 lo = *(const u32x2 *)vrow;
+                    const u32x2 hi = *(const u32x2 *)(vrow + 8);
+                    const u32x4 vv = {lo.x, lo.y, hi.x, hi.y};
+                    ov[e] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8, vv), pf, ov[e], 0, 0, 0);
+                }
+            }
+        }
+        run_sum += __shfl_xor(run_sum, 32, 64);
+        const float inv = 1.0f / run_sum;
+        _Float16 *out = (_Float16 *)p.C + (int64_t)(m0 + qrow) * p.ldc + head * ATT_DH;
+#pragma unroll
+        for (int e = 0; e < 2; ++e)
+#pragma unroll
+            for (int v4 = 0; v4 < 4; ++v4) {
+                half4 h;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) h[i] = (_Float16)(ov[e][v4 * 4 + i] * inv);
+                *(half4 *)(out + e * 32 + v4 * 8 + g * 4) = h;
+            }
+        return;
+    }
     if constexpr (KS == 2) {
         // second K group -> LDS -> first K group (same lane, same registers)
         float *part = (float *)smem_raw;
@@ -413,7 +544,7 @@ hipError_t launch_variant(const GemmProblem &p, const GemmBlocks &blocks, int N,
 template <int KIND, int RA, int NW, int KS>
 hipError_t launch_shape(const GemmProblem &p, const GemmBlocks &blocks, int N, hipStream_t stream)
 {
-    constexpr bool n_split = (KIND == GEMM_QKV || KIND == GEMM_FFN_UP);
+    constexpr bool n_split = (KIND == GEMM_QKV || KIND == GEMM_FFN_UP || KIND == GEMM_QKV_ATTN);
     if constexpr (!n_split && RA <= 2) {
         if (p.k_splits <= 1) return launch_variant<KIND, RA, NW, KS, true>(p, blocks, N, stream);
     }
@@ -424,14 +555,15 @@ template <int KIND, int RA, int NW, int KS, bool EARLY>
 hipError_t launch_variant(const GemmProblem &p, const GemmBlocks &blocks, int N, hipStream_t stream)
 {
     constexpr int BM = RA * 32, BN = NW * 32;
-    constexpr size_t lds = wide_lds_bytes<RA, NW, KS>();
+    constexpr size_t lds = (KIND == GEMM_QKV_ATTN && kAttentionLdsBytes > wide_lds_bytes<RA, NW, KS>())
+                               ? kAttentionLdsBytes : wide_lds_bytes<RA, NW, KS>();
     // once per instantiation, and safe when several host threads make their first call together
     static const hipError_t attr_status =
         hipFuncSetAttribute((const void *)gemm_wide_kernel<KIND, RA, NW, KS, EARLY>,
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (attr_status != hipSuccess) return attr_status;
     const int total = ((N + BN - 1) / BN) * ((p.T + BM - 1) / BM);
-    const bool n_split = (KIND == GEMM_QKV || KIND == GEMM_FFN_UP);
+    const bool n_split = (KIND == GEMM_QKV || KIND == GEMM_FFN_UP || KIND == GEMM_QKV_ATTN);
     dim3 grid(((total + 7) / 8) * 8, (!n_split && p.k_splits > 1) ? p.k_splits : 1);
     launch((gemm_wide_kernel<KIND, RA, NW, KS, EARLY>), grid, dim3(NW * KS * 64), lds, stream, p, blocks);
     return hipGetLastError();
@@ -445,6 +577,7 @@ hipError_t launch_kind(const GemmProblem &p, const GemmBlocks &blocks, int N, hi
     case GEMM_FFN_UP: return launch_shape<GEMM_FFN_UP, RA, NW, 1>(p, blocks, N, stream);
     case GEMM_OUT: return launch_shape<GEMM_OUT, RA, NW, 1>(p, blocks, N, stream);
     case GEMM_FFN_DOWN: return launch_shape<GEMM_FFN_DOWN, RA, NW, 1>(p, blocks, N, stream);
+    case GEMM_QKV_ATTN: break;   // one shape only, launched by launch_gemm_wide itself
     }
     return hipErrorInvalidValue;
 }
@@ -481,7 +614,7 @@ struct Choice {
 
 Choice choose(const GemmProblem &p, int N)
 {
-    const bool n_split = (p.kind == GEMM_QKV || p.kind == GEMM_FFN_UP);
+    const bool n_split = (p.kind == GEMM_QKV || p.kind == GEMM_FFN_UP || p.kind == GEMM_QKV_ATTN);
     int best = -1;
     long best_key[4] = {0, 0, 0, 0}, best_tiles = 0;
     for (int c = 0; c < (int)(sizeof(kShapes) / sizeof(kShapes[0])); ++c) {
@@ -523,7 +656,7 @@ Choice choose(const GemmProblem &p, int N)
 // the float32 partial sums than they save here).
 int gemm_wide_k_splits(const GemmProblem &p)
 {
-    if (p.kind == GEMM_QKV || p.kind == GEMM_FFN_UP || p.n_blocks <= 0 || p.T <= 0) return 1;
+    if (p.kind == GEMM_QKV || p.kind == GEMM_FFN_UP || p.kind == GEMM_QKV_ATTN || p.n_blocks <= 0 || p.T <= 0) return 1;
     const Choice ch = choose(p, p.block_rows);
     if (!ch.ks2) return 1;
     for (int s = 4; s >= 2; s >>= 1)
@@ -539,13 +672,25 @@ int gemm_wide_max_k_splits(int64_t T, int N)
     return 1;
 }
 
+// The fused form pays once its 128 x 384 tiles (one per sequence and pair of heads) fill at least
+// half of the compute units; below that the separate Q/K/V projection spreads over more of them.
+bool gemm_wide_fuses_attention(int B, int L, int m, int dh)
+{
+    return L == ATT_L && dh == ATT_DH && m > 0 && (int64_t)B * ((m + 1) / 2) >= kComputeUnits / 2;
+}
+
 hipError_t launch_gemm_wide(const GemmProblem &p, const GemmBlocks &blocks, hipStream_t stream)
 {
-    const bool n_split = (p.kind == GEMM_QKV || p.kind == GEMM_FFN_UP);
+    const bool n_split = (p.kind == GEMM_QKV || p.kind == GEMM_FFN_UP || p.kind == GEMM_QKV_ATTN);
     const int N = n_split ? p.n_blocks * p.block_rows : p.block_rows;
     if (p.T <= 0 || N <= 0) return hipSuccess;
     if (!gemm_wide_supported(p, blocks)) return hipErrorInvalidValue;
     if (N % 32 || p.block_rows % 32 || p.block_cols % BK || p.lda % 8 || p.ldc % 8) return hipErrorInvalidValue;
+    if (p.kind == GEMM_QKV_ATTN) {
+        if (p.T % ATT_L || p.block_rows != 3 * ATT_DH || p.d_head != ATT_DH || p.ldc < p.n_blocks * ATT_DH)
+            return hipErrorInvalidValue;
+        return launch_shape<GEMM_QKV_ATTN, 4, 12, 1>(p, blocks, N, stream);
+    }
     const Choice ch = choose(p, N);
     if (p.k_splits > 1 && (!ch.ks2 || p.k_splits != gemm_wide_k_splits(p))) return hipErrorInvalidValue;
     if (ch.ks2) {

@@ -58,7 +58,11 @@ enum GemmKind : int32_t {
     GEMM_QKV = 0,       // blocks along N: block p = [3*dh x d] (Wq,Wk,Wv of shard p); + bq|bk|bv
     GEMM_FFN_UP = 1,    // blocks along N: block p = [f x d];   + b1 slice, then GELU
     GEMM_OUT = 2,       // blocks along K: block p = [d x dh];  + bo[n] + residual
-    GEMM_FFN_DOWN = 3   // blocks along K: block p = [d x f];   + b2[n] + residual
+    GEMM_FFN_DOWN = 3,  // blocks along K: block p = [d x f];   + b2[n] + residual
+    // wide-tile kernel only, sequences of exactly 128 tokens: a 128 x 384 tile is the Q, K, V of
+    // two heads of one sequence, and the workgroup goes on to those heads' attention; C is then
+    // the context buffer [T x m*dh] and no Q/K/V buffer is written
+    GEMM_QKV_ATTN = 4
 };
 
 struct GemmBlock {
@@ -91,6 +95,7 @@ struct GemmProblem {
     // at C + s * partial_stride (bias and residual are left to launch_layernorm)
     int32_t k_splits;
     int64_t partial_stride;
+    const int32_t *key_lengths;   // GEMM_QKV_ATTN: real positions per sequence (device, may be null)
 };
 
 // float32 path (layer_f32.hip): A, C, resid are float32; weights are float32 blocks.
@@ -107,6 +112,8 @@ hipError_t launch_attention_f32(const float *qkv, float *ctx, int B, int L, int 
 // of the fragment-tiled binary16 working buffer (bits == kTiledBits).
 hipError_t launch_gemm_wide(const GemmProblem &p, const GemmBlocks &blocks, hipStream_t stream);
 bool gemm_wide_supported(const GemmProblem &p, const GemmBlocks &blocks);
+// whether the Q/K/V projection of B sequences of L tokens over m heads should go out as GEMM_QKV_ATTN
+bool gemm_wide_fuses_attention(int B, int L, int m, int dh);
 // K splits across workgroups the wide-tile kernel wants for this problem (1 = none), and the
 // largest value it can return for T tokens and N output columns (workspace sizing)
 int gemm_wide_k_splits(const GemmProblem &p);

@@ -784,6 +784,8 @@ def _run_masked(gpu, wl, prec, lens, route):
     ("mfma", MID, 9, 128, "model"),
     ("mfma", MID, 8, 200, "whole"),     # eight key blocks in registers, every layer's working buffer
     ("mfma", MID, 48, 128, "model"),    # four-wave workgroups
+    ("mfma", MID, 64, 128, "model"),    # attention inside the Q/K/V projection; 3 present heads: a tile with one head
+    ("mfma", WIDE, 24, 128, "whole"),   # the same with 11 present heads, every layer's working buffer
     ("mfma", MID, 7, 300, "whole"),     # online softmax
     ("mfma", MID, 2, 512, "model"),
 ])
@@ -802,6 +804,28 @@ def test_padded_sequences_match_the_reference(gpu, oracle_mod, prec, dims, B, L,
     assert rel_err(plain.float().cpu().numpy(), want) > 3 * TOL[prec]
     full = _run_masked(gpu, wl, prec, np.full(B, L, dtype=np.int32), route)
     assert torch.equal(full, plain)
+
+
+@pytest.mark.parametrize("dims,n_absent", [(MID, 1), (MID, 0), (WIDE, 3)])
+def test_attention_inside_the_projection_matches_the_separate_kernels(gpu, oracle_mod, dims, n_absent):
+    """With sequences of 128 tokens and enough of them, the Q/K/V projection's workgroups run the
+    attention of the two heads they hold.  Against the reference on every sequence (odd and even
+    numbers of present heads), and against the same sequences sent as four smaller batches, which take
+    the separate projection and attention kernels: the two compute the same values in the same order up
+    to the tile shapes that the batch size selects for the other projections."""
+    torch, P, D = gpu
+    B = 256 // ((dims.n_heads - n_absent + 1) // 2)
+    wl = S.small_workload(9100 + n_absent, dims, 2, B, 128, n_absent=n_absent, io_dtype="f16")
+    S.make_every_term_matter(wl, 12, amp=3.0)
+    want = oracle_mod.model_forward(dims, wl.shards, wl.params, wl.x)
+    got = run_gpu(gpu, wl, "mfma")
+    assert_parity(got, want, TOL["mfma"])
+    for b in (0, B // 2, B - 1):
+        assert_parity(got[b], want[b], TOL["mfma"], b)
+    q = B // 4
+    for part in range(4):
+        sub = run_gpu(gpu, wl, "mfma", x=wl.x[part * q:(part + 1) * q])
+        assert_parity(sub, got[part * q:(part + 1) * q], 4e-3, part)
 
 
 def test_padded_sequences_ignore_what_the_padding_holds(gpu):
