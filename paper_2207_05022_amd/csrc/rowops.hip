@@ -1,6 +1,7 @@
 // Row-wise and elementwise helpers of the layer: LayerNorm over d features
 // (biased variance, Section "A primer on transformer" runs stock BERT layers)
 // and activation type conversion.
+#include <type_traits>
 #include "sti_internal.hpp"
 
 namespace sti {
@@ -104,26 +105,58 @@ __global__ __launch_bounds__(256) void layernorm_vec_kernel(const float *pre, in
     const int row = blockIdx.x * ROWS + threadIdx.x / LPR;
     if (row >= T) return;   // whole row groups leave together; shuffles stay inside a group
     const int nchunk = d >> 2;
-    const f32x4 *r = (const f32x4 *)(pre + (int64_t)row * d);
+    // Every load of this row is independent of the others: they are issued in groups (bias and
+    // residual first, then the partial sums two planes at a time) and only then added, in the
+    // fixed order plane 0, 1, ..., bias, residual.  (Written as load-then-use per chunk, each of
+    // up to 8 planes x 8 chunks cost a round trip to memory of its own.)  Lanes past the end of
+    // the row load its last chunk and drop the value.
+    const int last = nchunk - 1;
+    int cj[MAXC];
+#pragma unroll
+    for (int j = 0; j < MAXC; ++j) cj[j] = min(sub + LPR * j, last);
+    f32x4 bs[MAXC];
+    half4 rs4[MAXC];
+#pragma unroll
+    for (int j = 0; j < MAXC; ++j) {
+        bs[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+        rs4[j] = half4{(_Float16)0.f, (_Float16)0.f, (_Float16)0.f, (_Float16)0.f};
+        if (bias) bs[j] = ((const f32x4 *)bias)[cj[j]];
+        if (resid) rs4[j] = ((const half4 *)(resid + (int64_t)row * d))[cj[j]];
+    }
+    f32x4 gg[MAXC], bb[MAXC];
+#pragma unroll
+    for (int j = 0; j < MAXC; ++j) {
+        gg[j] = ((const f32x4 *)g)[cj[j]];
+        bb[j] = ((const f32x4 *)b)[cj[j]];
+    }
     f32x4 v[MAXC];
+#pragma unroll
+    for (int j = 0; j < MAXC; ++j) v[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    const float *rp = pre + (int64_t)row * d;
+    for (int sp = 0; sp < n_partials; sp += 2) {
+        const bool two = sp + 1 < n_partials;   // uniform
+        f32x4 t0[MAXC], t1[MAXC];
+#pragma unroll
+        for (int j = 0; j < MAXC; ++j) {
+            t0[j] = *(const f32x4 *)(rp + (int64_t)sp * partial_stride + 4 * cj[j]);
+            t1[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+            if (two) t1[j] = *(const f32x4 *)(rp + (int64_t)(sp + 1) * partial_stride + 4 * cj[j]);
+        }
+#pragma unroll
+        for (int j = 0; j < MAXC; ++j) {
+            v[j] = sp == 0 ? t0[j] : v[j] + t0[j];
+            if (two) v[j] += t1[j];
+        }
+    }
     float s = 0.f;
 #pragma unroll
     for (int j = 0; j < MAXC; ++j) {
-        const int c = sub + LPR * j;
-        v[j] = f32x4{0.f, 0.f, 0.f, 0.f};
-        if (c < nchunk) {
-            f32x4 x = {0.f, 0.f, 0.f, 0.f};
-            if (n_partials > 0) x = r[c];
-            for (int sp = 1; sp < n_partials; ++sp)
-                x += *(const f32x4 *)(pre + (int64_t)sp * partial_stride + (int64_t)row * d + 4 * c);
-            if (bias) x += ((const f32x4 *)bias)[c];
-            if (resid) {
-                half4 h = ((const half4 *)(resid + (int64_t)row * d))[c];
-                x += f32x4{(float)h.x, (float)h.y, (float)h.z, (float)h.w};
-            }
-            v[j] = x;
-            s += (x.x + x.y) + (x.z + x.w);
-        }
+        f32x4 x = v[j];
+        if (bias) x += bs[j];
+        if (resid) x += f32x4{(float)rs4[j].x, (float)rs4[j].y, (float)rs4[j].z, (float)rs4[j].w};
+        if (sub + LPR * j >= nchunk) x = f32x4{0.f, 0.f, 0.f, 0.f};
+        v[j] = x;
+        s += (x.x + x.y) + (x.z + x.w);
     }
     const float mean = row_sum<LPR>(s) / (float)d;
     float q = 0.f;
@@ -141,8 +174,7 @@ __global__ __launch_bounds__(256) void layernorm_vec_kernel(const float *pre, in
     for (int j = 0; j < MAXC; ++j) {
         const int c = sub + LPR * j;
         if (c < nchunk) {
-            const f32x4 gg = ((const f32x4 *)g)[c], bb = ((const f32x4 *)b)[c];
-            const f32x4 t = (v[j] - mean) * inv * gg + bb;
+            const f32x4 t = (v[j] - mean) * inv * gg[j] + bb[j];
             if constexpr (DT == STI_F32) {
                 ((f32x4 *)o)[c] = t;
             } else if constexpr (DT == STI_F16) {
@@ -156,61 +188,65 @@ __global__ __launch_bounds__(256) void layernorm_vec_kernel(const float *pre, in
 }
 
 // LayerNorm of rows that already hold sum + bias + residual in binary16 (written by the
-// matrix-core GEMM); d a multiple of 8 and at most 2048 (longer rows: the kernel after this
-// one); one wave per row.
-template <int DT>
+// matrix-core GEMM); d a multiple of 8 and at most 8 * LPR * MAXC; LPR lanes per row.  All
+// loads (the row, gains, shifts) are issued before the first use: one round trip to memory.
+// Lanes past the end of the row load its last chunk and drop the value.
+template <int DT, int LPR, int MAXC>
 __global__ __launch_bounds__(256) void layernorm_f16in_kernel(const _Float16 *pre,
                                                               typename Elem<DT>::type *y,
                                                               const float *g, const float *b, int T,
                                                               int d, float eps)
 {
-    constexpr int MAXC = 4;   // 8-element chunks per lane
     typedef _Float16 half8 __attribute__((ext_vector_type(8)));
-    const int lane = threadIdx.x % 64;
-    const int row = blockIdx.x * 4 + threadIdx.x / 64;
-    if (row >= T) return;
-    const int nchunk = d >> 3;
+    constexpr int ROWS = 256 / LPR;
+    const int sub = threadIdx.x % LPR;
+    const int row = blockIdx.x * ROWS + threadIdx.x / LPR;
+    if (row >= T) return;   // whole row groups leave together; shuffles stay inside a group
+    const int nchunk = d >> 3, last = nchunk - 1;
     const half8 *r = (const half8 *)(pre + (int64_t)row * d);
+    half8 h[MAXC];
+    f32x4 g0[MAXC], g1[MAXC], b0[MAXC], b1[MAXC];
+#pragma unroll
+    for (int j = 0; j < MAXC; ++j) h[j] = r[min(sub + LPR * j, last)];
+#pragma unroll
+    for (int j = 0; j < MAXC; ++j) {
+        const int c = min(sub + LPR * j, last);
+        g0[j] = ((const f32x4 *)g)[2 * c]; g1[j] = ((const f32x4 *)g)[2 * c + 1];
+        b0[j] = ((const f32x4 *)b)[2 * c]; b1[j] = ((const f32x4 *)b)[2 * c + 1];
+    }
     float v[MAXC][8];
     float s = 0.f;
 #pragma unroll
     for (int j = 0; j < MAXC; ++j) {
-        const int c = lane + 64 * j;
+        const bool in = sub + LPR * j < nchunk;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) v[j][e] = 0.f;
-        if (c < nchunk) {
-            const half8 h = r[c];
-#pragma unroll
-            for (int e = 0; e < 8; ++e) { v[j][e] = (float)h[e]; s += v[j][e]; }
-        }
+        for (int e = 0; e < 8; ++e) { v[j][e] = in ? (float)h[j][e] : 0.f; s += v[j][e]; }
     }
-    const float mean = wave_sum(s) / (float)d;
+    const float mean = row_sum<LPR>(s) / (float)d;
     float q = 0.f;
 #pragma unroll
     for (int j = 0; j < MAXC; ++j)
-        if (lane + 64 * j < nchunk) {
+        if (sub + LPR * j < nchunk) {
 #pragma unroll
             for (int e = 0; e < 8; ++e) { const float t = v[j][e] - mean; q = fmaf(t, t, q); }
         }
-    const float var = wave_sum(q) / (float)d;
+    const float var = row_sum<LPR>(q) / (float)d;
     const float inv = 1.0f / sqrtf(var + eps);
     typename Elem<DT>::type *o = y + (int64_t)row * d;
 #pragma unroll
     for (int j = 0; j < MAXC; ++j) {
-        const int c = lane + 64 * j;
+        const int c = sub + LPR * j;
         if (c < nchunk) {
-            const f32x4 g0 = ((const f32x4 *)g)[2 * c], g1 = ((const f32x4 *)g)[2 * c + 1];
-            const f32x4 b0 = ((const f32x4 *)b)[2 * c], b1 = ((const f32x4 *)b)[2 * c + 1];
-            const float gg[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
-            const float bb[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
+            const float gg[8] = {g0[j].x, g0[j].y, g0[j].z, g0[j].w, g1[j].x, g1[j].y, g1[j].z, g1[j].w};
+            const float bb[8] = {b0[j].x, b0[j].y, b0[j].z, b0[j].w, b1[j].x, b1[j].y, b1[j].z, b1[j].w};
             float t[8];
 #pragma unroll
             for (int e = 0; e < 8; ++e) t[e] = (v[j][e] - mean) * inv * gg[e] + bb[e];
             if constexpr (DT == STI_F16) {
-                half8 h;
+                half8 o8;
 #pragma unroll
-                for (int e = 0; e < 8; ++e) h[e] = (_Float16)t[e];
-                ((half8 *)o)[c] = h;
+                for (int e = 0; e < 8; ++e) o8[e] = (_Float16)t[e];
+                ((half8 *)o)[c] = o8;
             } else {
 #pragma unroll
                 for (int e = 0; e < 8; ++e) Elem<DT>::store(o + 8 * c + e, t[e]);
@@ -293,13 +329,22 @@ void launch_ln_typed(const float *pre, int n_partials, int64_t partial_stride, c
 {
     typedef typename Elem<DT>::type O;
     dim3 grid((T + 3) / 4);
-    // many rows: 16 lanes per row (16 rows per workgroup); few rows: a whole wave per row
-    if (vec && T >= 2048 && d <= 1024)
-        launch((layernorm_vec_kernel<DT, 32, 8>), dim3((T + 7) / 8), dim3(256), 0, stream, pre, n_partials, partial_stride, bias, (const _Float16 *)resid, (O *)y, g, b, T, d, eps);
-    else if (vec)
-        launch((layernorm_vec_kernel<DT, 64, 8>), grid, dim3(256), 0, stream, pre, n_partials, partial_stride, bias, (const _Float16 *)resid, (O *)y, g, b, T, d, eps);
-    else
+#define STI_LN_VEC(LPR, MAXC, GRID) \
+    launch((layernorm_vec_kernel<DT, LPR, MAXC>), GRID, dim3(256), 0, stream, pre, n_partials, partial_stride, bias, \
+           (const _Float16 *)resid, (O *)y, g, b, T, d, eps)
+    // many rows: 32 lanes per row (8 rows per workgroup); few rows: a whole wave per row; chunks
+    // per lane sized to the row, so that the registers hold no more loads in flight than it has
+    if (vec && T >= 2048 && d <= 1024) {
+        if (d <= 768) STI_LN_VEC(32, 6, dim3((T + 7) / 8));
+        else STI_LN_VEC(32, 8, dim3((T + 7) / 8));
+    } else if (vec) {
+        if (d <= 768) STI_LN_VEC(64, 3, grid);
+        else if (d <= 1024) STI_LN_VEC(64, 4, grid);
+        else STI_LN_VEC(64, 8, grid);
+    } else {
         launch((layernorm_kernel<DT>), grid, dim3(256), 0, stream, pre, n_partials, partial_stride, bias, (const _Float16 *)resid, (O *)y, g, b, T, d, eps);
+    }
+#undef STI_LN_VEC
 }
 
 hipError_t launch_layernorm(const float *pre, int n_partials, int64_t partial_stride,
@@ -335,10 +380,22 @@ hipError_t launch_layernorm_f16in(const void *pre_f16, void *y, sti_dtype out_dt
         }
         return hipGetLastError();
     }
+    // 32 lanes per row while the row fits 3 or 4 chunks of 8 per lane (every lane busy at d_model 768
+    // and 1024), a whole wave per row beyond
+    auto go = [&](auto dt) {
+        constexpr int DT = decltype(dt)::value;
+        typedef typename Elem<DT>::type O;
+        if (d <= 768)
+            launch((layernorm_f16in_kernel<DT, 32, 3>), dim3((T + 7) / 8), dim3(256), 0, stream, p, (O *)y, g, b, T, d, eps);
+        else if (d <= 1024)
+            launch((layernorm_f16in_kernel<DT, 32, 4>), dim3((T + 7) / 8), dim3(256), 0, stream, p, (O *)y, g, b, T, d, eps);
+        else
+            launch((layernorm_f16in_kernel<DT, 64, 4>), dim3((T + 3) / 4), dim3(256), 0, stream, p, (O *)y, g, b, T, d, eps);
+    };
     switch (out_dtype) {
-        case STI_F32: launch((layernorm_f16in_kernel<STI_F32>), grid, dim3(256), 0, stream, p, (float *)y, g, b, T, d, eps); break;
-        case STI_F16: launch((layernorm_f16in_kernel<STI_F16>), grid, dim3(256), 0, stream, p, (_Float16 *)y, g, b, T, d, eps); break;
-        case STI_BF16: launch((layernorm_f16in_kernel<STI_BF16>), grid, dim3(256), 0, stream, p, (uint16_t *)y, g, b, T, d, eps); break;
+        case STI_F32: go(std::integral_constant<int, STI_F32>{}); break;
+        case STI_F16: go(std::integral_constant<int, STI_F16>{}); break;
+        case STI_BF16: go(std::integral_constant<int, STI_BF16>{}); break;
     }
     return hipGetLastError();
 }
