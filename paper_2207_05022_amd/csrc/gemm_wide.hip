@@ -84,7 +84,13 @@ constexpr size_t wide_lds_bytes()
 // hands its accumulators over through LDS at the end.  Twice the waves per compute unit for
 // a tile count that is fixed by the output size.
 template <int KIND, int RA, int NW, int KS, bool EARLY>
-__global__ __launch_bounds__(NW * KS * 64, 3) void gemm_wide_kernel(GemmProblem p, GemmBlocks blocks)
+__global__ __launch_bounds__(NW * KS * 64, 3) void gemm_wide_kernel(
+    // what the first loads of a workgroup depend on, as leading scalar arguments: these arrive
+    // preloaded in scalar registers (the build asks for kernel-argument preloading), so that the
+    // first A fetches and weight loads are not behind a round trip to the argument buffer
+    const void *hot_A, const void *hot_w0, int64_t hot_w_stride, int32_t hot_T, int32_t hot_lda,
+    int32_t hot_n_blocks, int32_t hot_block_rows, int32_t hot_block_cols, int32_t hot_k_splits,
+    GemmProblem p, GemmBlocks blocks)   // (of p, only the fields that are not among the leading arguments are read)
 {
     constexpr int BM = RA * 32, BN = NW * 32, NT = NW * KS * 64, NTH = NW * 64;
     constexpr bool n_split = (KIND == GEMM_QKV || KIND == GEMM_FFN_UP || KIND == GEMM_QKV_ATTN);
@@ -96,11 +102,11 @@ __global__ __launch_bounds__(NW * KS * 64, 3) void gemm_wide_kernel(GemmProblem 
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
     _Float16 *a_lds = (_Float16 *)smem_raw;
 
-    const int N = n_split ? p.n_blocks * p.block_rows : p.block_rows;
-    const int K = n_split ? p.block_cols : p.n_blocks * p.block_cols;
+    const int N = n_split ? hot_n_blocks * hot_block_rows : hot_block_rows;
+    const int K = n_split ? hot_block_cols : hot_n_blocks * hot_block_cols;
     // K is split over the KS wave groups of the workgroup and, for few tiles, over
     // gridDim.y workgroups per tile as well (raw float32 partial sums, see the epilogue)
-    const int splits = (!n_split && p.k_splits > 1) ? p.k_splits : 1;
+    const int splits = (!n_split && hot_k_splits > 1) ? hot_k_splits : 1;
     const int nkt = K / BK / KS / splits;  // K tiles of this wave's group
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave_all = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -115,7 +121,7 @@ __global__ __launch_bounds__(NW * KS * 64, 3) void gemm_wide_kernel(GemmProblem 
     // (measured at d_model 2048, 4096 tokens: 720 -> 617 us per layer; at 8 to 11 column
     // tiles the two orders measure the same within run-to-run noise).
     const int n_tiles = (N + BN - 1) / BN;
-    const int m_tiles = (p.T + BM - 1) / BM;
+    const int m_tiles = (hot_T + BM - 1) / BM;
     const int total_tiles = n_tiles * m_tiles;
     const int per_xcd = (total_tiles + 7) / 8;
     const int tile = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
@@ -134,10 +140,10 @@ __global__ __launch_bounds__(NW * KS * 64, 3) void gemm_wide_kernel(GemmProblem 
     const int nw = nw_real < N ? nw_real : 0;
     int nblk = 0, nrow0 = nw;
     if (n_split) {
-        nblk = nw / p.block_rows;
-        nrow0 = nw - nblk * p.block_rows;
+        nblk = nw / hot_block_rows;
+        nrow0 = nw - nblk * hot_block_rows;
     }
-    const int tiles_per_kblock = n_split ? nkt * KS : p.block_cols / BK;
+    const int tiles_per_kblock = n_split ? nkt * KS : hot_block_cols / BK;
 
     float16v acc[RA];
 #pragma unroll
@@ -149,13 +155,13 @@ __global__ __launch_bounds__(NW * KS * 64, 3) void gemm_wide_kernel(GemmProblem 
     //      rows with the chunk (l%8) ^ ((row/2)%8) of that row, so that the 16 rows that one
     //      quarter of a fragment read touches (128-byte rows, two per 64-bank line) fall on
     //      16 different bank groups; rows past T repeat row T-1 ----
-    const _Float16 *A = (const _Float16 *)p.A + (int64_t)m0 * p.lda;   // first row of the tile
+    const _Float16 *A = (const _Float16 *)hot_A + (int64_t)m0 * hot_lda;   // first row of the tile
     uint32_t src[FPW];   // byte offset of this lane's chunk from the tile's first row and K tile
 #pragma unroll
     for (int j = 0; j < FPW; ++j) {
         const int row = (wave + NW * j) * 8 + (lane >> 3);   // row inside the tile
-        const int r = m0 + row < p.T ? row : p.T - 1 - m0;
-        src[j] = (uint32_t)((r * p.lda + (((lane & 7) ^ ((row >> 1) & 7)) * 8)) * 2);   // < 2^24 * 2
+        const int r = m0 + row < hot_T ? row : hot_T - 1 - m0;
+        src[j] = (uint32_t)((r * hot_lda + (((lane & 7) ^ ((row >> 1) & 7)) * 8)) * 2);   // < 2^24 * 2
     }
     // The loads of the K loop are written as instructions rather than through the compiler:
     // its own bookkeeping would wait for every outstanding fetch into LDS before the next LDS
@@ -186,8 +192,9 @@ __global__ __launch_bounds__(NW * KS * 64, 3) void gemm_wide_kernel(GemmProblem 
         } else {
             blk = kt / tiles_per_kblock; ktb = kt - blk * tiles_per_kblock; row = nw;
         }
-        const uint8_t *base = (const uint8_t *)blocks.b[blk].w;
-        return base + tiled_cell_offset(row >> 5, ktb, p.block_cols);   // wave-uniform
+        // (the blocks of a working buffer lie at a constant distance: no look-up in the block table)
+        const uint8_t *base = (const uint8_t *)hot_w0 + (int64_t)blk * hot_w_stride;
+        return base + tiled_cell_offset(row >> 5, ktb, hot_block_cols);   // wave-uniform
     };
 
     // Three A stages and three sets of weight fragment registers: the loads of K tile t+2 are
@@ -230,7 +237,7 @@ __global__ __launch_bounds__(NW * KS * 64, 3) void gemm_wide_kernel(GemmProblem 
                 const int which = nrow / p.d_head, e0 = nrow - which * p.d_head;
                 bp = (which == 0 ? p.bias0 : (which == 1 ? p.bias1 : p.bias2)) + blocks.b[nblk].shard * p.d_head + e0;
             } else if constexpr (KIND == GEMM_FFN_UP) {
-                bp = p.bias0 + blocks.b[nblk].shard * p.block_rows + nrow0 + c;
+                bp = p.bias0 + blocks.b[nblk].shard * hot_block_rows + nrow0 + c;
             } else {
                 bp = p.bias0 + nw + c;
             }
@@ -244,7 +251,7 @@ __global__ __launch_bounds__(NW * KS * 64, 3) void gemm_wide_kernel(GemmProblem 
 #pragma unroll
                 for (int q = 0; q < 2; ++q) {
                     u32x4 v = {0, 0, 0, 0};
-                    if (m < p.T) v = *(const u32x4 *)(R + (int64_t)m * p.ldr + nw + 16 * q + 8 * g);
+                    if (m < hot_T) v = *(const u32x4 *)(R + (int64_t)m * p.ldr + nw + 16 * q + 8 * g);
                     resv[i][q] = v;
                 }
             }
@@ -346,7 +353,7 @@ __global__ __launch_bounds__(NW * KS * 64, 3) void gemm_wide_kernel(GemmProblem 
         }
         __syncthreads();
         const int head = tile_n * 2 + (wave >> 2);          // present-head index of waves 0..7
-        if (wave >= 8 || head >= p.n_blocks) return;
+        if (wave >= 8 || head >= hot_n_blocks) return;
         hb = (_Float16 *)smem_raw + (wave >> 2) * ATT_HEAD_HALVES;
         const _Float16 *Qs = hb, *Ks = hb + ATT_L * ATT_KPAD, *Vt = hb + 2 * (ATT_L * ATT_KPAD);
         int Lk = ATT_L;
@@ -466,7 +473,7 @@ __global__ __launch_bounds__(NW * KS * 64, 3) void gemm_wide_kernel(GemmProblem 
                         x[e] = __builtin_bit_cast(float, s0);
                         x[4 + e] = __builtin_bit_cast(float, s1);
                     }
-                    if (m < p.T) {
+                    if (m < hot_T) {
                         float *dst = Cf + (int64_t)m * p.ldc + nw + 16 * q + 8 * g;
                         *(f32x4 *)dst = f32x4{x[0], x[1], x[2], x[3]};
                         *(f32x4 *)(dst + 4) = f32x4{x[4], x[5], x[6], x[7]};
@@ -489,7 +496,7 @@ __global__ __launch_bounds__(NW * KS * 64, 3) void gemm_wide_kernel(GemmProblem 
 #pragma unroll
             for (int q = 0; q < 2; ++q) {
                 u32x4 v = {0, 0, 0, 0};
-                if (m < p.T) v = *(const u32x4 *)(R + (int64_t)m * p.ldr + nw + 16 * q + 8 * g);
+                if (m < hot_T) v = *(const u32x4 *)(R + (int64_t)m * p.ldr + nw + 16 * q + 8 * g);
                 res[q] = __builtin_bit_cast(half8, v);
             }
         }
@@ -534,7 +541,7 @@ __global__ __launch_bounds__(NW * KS * 64, 3) void gemm_wide_kernel(GemmProblem 
     for (int j = 0; j < PASSES; ++j) {
         const int pc = tid + NT * j;
         const int m = m0 + pc / PIECES_PER_ROW, n = tile_n * BN + (pc % PIECES_PER_ROW) * 8;
-        if (m < p.T && n < N) *(u32x4 *)(C + (int64_t)m * p.ldc + n) = piece[j];
+        if (m < hot_T && n < N) *(u32x4 *)(C + (int64_t)m * p.ldc + n) = piece[j];
     }
 }
 
@@ -565,7 +572,9 @@ hipError_t launch_variant(const GemmProblem &p, const GemmBlocks &blocks, int N,
     const int total = ((N + BN - 1) / BN) * ((p.T + BM - 1) / BM);
     const bool n_split = (KIND == GEMM_QKV || KIND == GEMM_FFN_UP || KIND == GEMM_QKV_ATTN);
     dim3 grid(((total + 7) / 8) * 8, (!n_split && p.k_splits > 1) ? p.k_splits : 1);
-    launch((gemm_wide_kernel<KIND, RA, NW, KS, EARLY>), grid, dim3(NW * KS * 64), lds, stream, p, blocks);
+    const int64_t w_stride = p.n_blocks > 1 ? (const uint8_t *)blocks.b[1].w - (const uint8_t *)blocks.b[0].w : 0;
+    launch((gemm_wide_kernel<KIND, RA, NW, KS, EARLY>), grid, dim3(NW * KS * 64), lds, stream, p.A, blocks.b[0].w,
+           w_stride, p.T, p.lda, p.n_blocks, p.block_rows, p.block_cols, p.k_splits, p, blocks);
     return hipGetLastError();
 }
 
@@ -600,6 +609,10 @@ bool gemm_wide_supported(const GemmProblem &p, const GemmBlocks &blocks)
     if (p.n_blocks <= 0 || p.T <= 0) return false;
     for (int b = 0; b < p.n_blocks; ++b)
         if (blocks.b[b].bits != kTiledBits) return false;
+    // the kernel addresses block b as block 0 + b * (distance of the first two)
+    const int64_t stride = p.n_blocks > 1 ? (const uint8_t *)blocks.b[1].w - (const uint8_t *)blocks.b[0].w : 0;
+    for (int b = 2; b < p.n_blocks; ++b)
+        if ((const uint8_t *)blocks.b[b].w - (const uint8_t *)blocks.b[0].w != stride * b) return false;
     return true;
 }
 
