@@ -43,13 +43,17 @@ struct SkinnySmem {
 
 // grid: x = 32-column strip, y = K split, z = 64-row block of A
 template <int RA>
-__global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(GemmProblem p, GemmBlocks blocks,
-                                                          int k_splits, int64_t partial_stride)
+__global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(
+    // leading scalar arguments arrive preloaded in scalar registers: what the first loads of a
+    // workgroup depend on (of p, only the other fields are read)
+    const void *hot_A, int32_t hot_T, int32_t hot_lda, int32_t hot_n_blocks, int32_t hot_block_rows,
+    int32_t hot_block_cols, int32_t hot_kind, int32_t k_splits, int64_t partial_stride,
+    GemmProblem p, GemmBlocks blocks)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     SkinnySmem<RA> &sm = *reinterpret_cast<SkinnySmem<RA> *>(smem_raw);
-    const bool n_split = (p.kind == GEMM_QKV || p.kind == GEMM_FFN_UP);
-    const int K = n_split ? p.block_cols : p.n_blocks * p.block_cols;
+    const bool n_split = (hot_kind == GEMM_QKV || hot_kind == GEMM_FFN_UP);
+    const int K = n_split ? hot_block_cols : hot_n_blocks * hot_block_cols;
     const int nkt = K / BK;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -60,7 +64,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(GemmProblem p, Gem
     const int kt_begin = (int)((int64_t)nkt * split / k_splits);
     const int kt_end = (int)((int64_t)nkt * (split + 1) / k_splits);
 
-    for (int i = tid; i < p.n_blocks * kLutEntries; i += NW * 64) {
+    for (int i = tid; i < hot_n_blocks * kLutEntries; i += NW * 64) {
         const int b = i / kLutEntries, e = i % kLutEntries;
         const int bits = blocks.b[b].bits;
         if (bits <= 6 && e < (1 << bits)) sm.lut[b][e] = (uint16_t)f16_bits(blocks.b[b].codebook[e]);
@@ -68,10 +72,10 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(GemmProblem p, Gem
 
     int nblk = 0, nrow0 = nw;
     if (n_split) {
-        nblk = nw / p.block_rows;
-        nrow0 = nw - nblk * p.block_rows;
+        nblk = nw / hot_block_rows;
+        nrow0 = nw - nblk * hot_block_rows;
     }
-    const int tiles_per_kblock = n_split ? nkt : p.block_cols / BK;
+    const int tiles_per_kblock = n_split ? nkt : hot_block_cols / BK;
 
     struct BStage {
         Raw raw;
@@ -89,9 +93,9 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(GemmProblem p, Gem
         st.bits = bits; st.blk = blk;
         const uint8_t *base = (const uint8_t *)blocks.b[blk].w;
         if (bits == kTiledBits) {
-            st.raw = load_tiled(base + tiled_cell_offset(row >> 5, ktb, p.block_cols), lane);
+            st.raw = load_tiled(base + tiled_cell_offset(row >> 5, ktb, hot_block_cols), lane);
         } else {
-            const int64_t elem = (int64_t)(row + lr) * p.block_cols + ktb * BK + g * 32;
+            const int64_t elem = (int64_t)(row + lr) * hot_block_cols + ktb * BK + g * 32;
             st.raw = load_raw_any(bits, base + (elem >> 5) * (bits * 4));
         }
         return st;
@@ -99,17 +103,17 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(GemmProblem p, Gem
     struct AStage {
         u32x4 f[RA][4];
     };
-    const _Float16 *A = (const _Float16 *)p.A;
+    const _Float16 *A = (const _Float16 *)hot_A;
     auto fetch_a = [&](int kt) -> AStage {
         AStage st;
 #pragma unroll
         for (int i = 0; i < RA; ++i) {
             const int m = m0 + i * 32 + lr;
-            const _Float16 *src = A + (int64_t)m * p.lda + kt * BK + g * 32;
+            const _Float16 *src = A + (int64_t)m * hot_lda + kt * BK + g * 32;
 #pragma unroll
             for (int s = 0; s < 4; ++s) {
                 u32x4 v = {0, 0, 0, 0};
-                if (m < p.T) v = *(const u32x4 *)(src + s * 8);
+                if (m < hot_T) v = *(const u32x4 *)(src + s * 8);
                 st.f[i][s] = v;
             }
         }
@@ -154,12 +158,12 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(GemmProblem p, Gem
     float bias = 0.f;
     if (n_split) {
         const int nrow = nrow0 + lr;
-        if (p.kind == GEMM_QKV) {
+        if (hot_kind == GEMM_QKV) {
             const int which = nrow / p.d_head, e = nrow - which * p.d_head;
             const float *bp = which == 0 ? p.bias0 : (which == 1 ? p.bias1 : p.bias2);
             bias = bp[blocks.b[nblk].shard * p.d_head + e];
         } else {
-            bias = p.bias0[blocks.b[nblk].shard * p.block_rows + nrow];
+            bias = p.bias0[blocks.b[nblk].shard * hot_block_rows + nrow];
         }
     }
 #pragma unroll
@@ -178,14 +182,14 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(GemmProblem p, Gem
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int m = m0 + i * 32 + (v >> 2) * 8 + g * 4 + (v & 3);
-                if (m < p.T) C[(int64_t)m * p.ldc + nw + lr] = sum[v];
+                if (m < hot_T) C[(int64_t)m * p.ldc + nw + lr] = sum[v];
             }
         } else {
             _Float16 *st = &sm.stage[wave][0][0];
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 float x = sum[v] + bias;
-                if (p.kind == GEMM_FFN_UP) x = gelu_fast(x);
+                if (hot_kind == GEMM_FFN_UP) x = gelu_fast(x);
                 st[((v >> 2) * 8 + g * 4 + (v & 3)) * 40 + lr] = (_Float16)x;
             }
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -197,7 +201,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(GemmProblem p, Gem
                 const int c = lane + 64 * j;   // 16-byte chunk of the 32 x 32 tile
                 const int row = c >> 2, cc = c & 3;
                 const int m = m0 + i * 32 + row;
-                if (m < p.T)
+                if (m < hot_T)
                     *(u32x4 *)(C + (int64_t)m * p.ldc + nw + cc * 8) = *(const u32x4 *)(st + row * 40 + cc * 8);
             }
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -218,8 +222,8 @@ hipError_t launch_ra(const GemmProblem &p, const GemmBlocks &blocks, int N, int 
         hipFuncSetAttribute((const void *)gemm_skinny_kernel<RA>, hipFuncAttributeMaxDynamicSharedMemorySize,
                             (int)sizeof(SkinnySmem<RA>));
     if (attr_status != hipSuccess) return attr_status;
-    launch((gemm_skinny_kernel<RA>), grid, dim3(NW * 64), sizeof(SkinnySmem<RA>), stream, p, blocks, k_splits,
-                                                                              partial_stride);
+    launch((gemm_skinny_kernel<RA>), grid, dim3(NW * 64), sizeof(SkinnySmem<RA>), stream, p.A, p.T, p.lda, p.n_blocks,
+           p.block_rows, p.block_cols, (int32_t)p.kind, k_splits, partial_stride, p, blocks);
     return hipGetLastError();
 }
 
