@@ -37,7 +37,7 @@ __device__ inline float gelu_fast(float z)
 template <int RA>
 struct SkinnySmem {
     float red[NW][RA][16][64];                       // partial accumulators of the waves
-    uint16_t lut[kMaxShardsPerLayer][kLutEntries];   // codebooks as binary16
+    uint16_t lut[NW][2][kLutEntries];                // codebooks (binary16) of each wave's current and next tile
     _Float16 stage[NW][32][40];                      // output staging, one 32 x 32 tile per wave
 };
 
@@ -64,12 +64,6 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(
     const int kt_begin = (int)((int64_t)nkt * split / k_splits);
     const int kt_end = (int)((int64_t)nkt * (split + 1) / k_splits);
 
-    for (int i = tid; i < hot_n_blocks * kLutEntries; i += NW * 64) {
-        const int b = i / kLutEntries, e = i % kLutEntries;
-        const int bits = blocks.b[b].bits;
-        if (bits <= 6 && e < (1 << bits)) sm.lut[b][e] = (uint16_t)f16_bits(blocks.b[b].codebook[e]);
-    }
-
     int nblk = 0, nrow0 = nw;
     if (n_split) {
         nblk = nw / hot_block_rows;
@@ -79,9 +73,12 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(
 
     struct BStage {
         Raw raw;
-        int bits, blk;
+        int bits;
+        float centroid;   // entry `lane` of the block's codebook (k-bit blocks)
     };
-    auto fetch_b = [&](int kt) -> BStage {
+    // weight block of K tile kt (wave-uniform)
+    auto block_of = [&](int kt) -> int { return n_split ? nblk : kt / tiles_per_kblock; };
+    auto fetch_b = [&](int kt, const GemmBlock &desc) -> BStage {
         BStage st;
         int blk, ktb, row;
         if (n_split) {
@@ -89,9 +86,13 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(
         } else {
             blk = kt / tiles_per_kblock; ktb = kt - blk * tiles_per_kblock; row = nw;
         }
-        const int bits = blocks.b[blk].bits;
-        st.bits = bits; st.blk = blk;
-        const uint8_t *base = (const uint8_t *)blocks.b[blk].w;
+        const int bits = desc.bits;
+        st.bits = bits;
+        // this lane's centroid first: staging it into LDS then waits for this load only, not for
+        // the weights behind it (blocks without a codebook read the activations: valid memory,
+        // value unused)
+        st.centroid = *(bits <= 6 ? desc.codebook + (lane & ((1 << bits) - 1)) : (const float *)hot_A + lane);
+        const uint8_t *base = (const uint8_t *)desc.w;
         if (bits == kTiledBits) {
             st.raw = load_tiled(base + tiled_cell_offset(row >> 5, ktb, hot_block_cols), lane);
         } else {
@@ -108,14 +109,10 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(
         AStage st;
 #pragma unroll
         for (int i = 0; i < RA; ++i) {
-            const int m = m0 + i * 32 + lr;
+            const int m = min(m0 + i * 32 + lr, hot_T - 1);   // rows past T repeat row T-1; their results are not stored
             const _Float16 *src = A + (int64_t)m * hot_lda + kt * BK + g * 32;
 #pragma unroll
-            for (int s = 0; s < 4; ++s) {
-                u32x4 v = {0, 0, 0, 0};
-                if (m < hot_T) v = *(const u32x4 *)(src + s * 8);
-                st.f[i][s] = v;
-            }
+            for (int s = 0; s < 4; ++s) st.f[i][s] = *(const u32x4 *)(src + s * 8);
         }
         return st;
     };
@@ -126,20 +123,47 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
 
-    // two tiles in flight before anything else is waited for
+    // Two tiles in flight before anything else is waited for.  Order of the requests: the A
+    // fragments (they need nothing but the leading arguments), then every block descriptor this
+    // wave will look at (those of its first two tiles and of the codebooks it stages) in one
+    // round of scalar loads, then the weights, then the centroids.
     int kt = kt_begin + wave;
     AStage a_cur, a_nxt;
     BStage b_cur, b_nxt;
-    if (kt < kt_end) { b_cur = fetch_b(kt); a_cur = fetch_a(kt); }
-    if (kt + NW < kt_end) { b_nxt = fetch_b(kt + NW); a_nxt = fetch_a(kt + NW); }
-    __syncthreads();   // codebooks visible
-    for (; kt < kt_end; kt += NW) {
+    if (kt < kt_end) a_cur = fetch_a(kt);
+    if (kt + NW < kt_end) a_nxt = fetch_a(kt + NW);
+    const int last_blk = hot_n_blocks - 1;
+    const GemmBlock desc0 = blocks.b[min(block_of(min(kt, nkt - 1)), last_blk)];
+    const GemmBlock desc1 = blocks.b[min(block_of(min(kt + NW, nkt - 1)), last_blk)];
+    if (kt < kt_end) b_cur = fetch_b(kt, desc0);
+    if (kt + NW < kt_end) b_nxt = fetch_b(kt + NW, desc1);
+    // Each wave keeps the codebooks of its own current and next tile in LDS (binary16): no
+    // workgroup-wide table, no barrier, and no descriptor beyond those of the tiles themselves.
+    static_assert(kLutEntries == 64, "one lane per centroid");
+    auto stage_lut = [&](int slot, const BStage &st) {
+        if (st.bits <= 6) sm.lut[wave][slot][lane] = (uint16_t)f16_bits(st.centroid);
+    };
+    if (kt < kt_end) stage_lut(0, b_cur);
+    if (kt + NW < kt_end) stage_lut(1, b_nxt);
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    for (int slot = 0; kt < kt_end; kt += NW, slot ^= 1) {
         const BStage bs = b_cur;
         const AStage as = a_cur;
         b_cur = b_nxt; a_cur = a_nxt;
-        if (kt + 2 * NW < kt_end) { b_nxt = fetch_b(kt + 2 * NW); a_nxt = fetch_a(kt + 2 * NW); }
         half8 bf[4];
-        decode_raw_any(bs.bits, bs.raw, sm.lut[bs.blk], bf);
+        decode_raw_any(bs.bits, bs.raw, sm.lut[wave][slot], bf);
+        if (kt + 2 * NW < kt_end) {   // (a third tile per wave: rare; its codebook takes the slot just read)
+            b_nxt = fetch_b(kt + 2 * NW, blocks.b[block_of(kt + 2 * NW)]);
+            a_nxt = fetch_a(kt + 2 * NW);
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            stage_lut(slot, b_nxt);
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        }
 #pragma unroll
         for (int s = 0; s < 4; ++s)
 #pragma unroll
