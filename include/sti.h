@@ -438,8 +438,14 @@ sti_status sti_plan_bitwidths(const sti_plan_tables *tables, int32_t n, int32_t 
  *  stats          DEVICE out, may be NULL; status 1 = every weight is an outlier
  *                 (nothing to cluster; packed and codebook are meaningless).
  *  workspace      DEVICE, >= sti_quantize_workspace_bytes(dims), 256-byte aligned.
- * Statistics are accumulated in float64 in a fixed order: a call is reproducible
- * bit for bit.  Errors as for the other entry points.
+ * The moments (mean, variance) are accumulated in float64 in a fixed order.  The
+ * cluster sums are float64 too; within one wave the order in which weights of one
+ * cluster are added is the hardware's (LDS atomics), the per-wave sums are then
+ * combined in a fixed order.  Any order of such a sum of at most 256 float32 values
+ * agrees to about 1e-16 relative, far below the one float32 rounding of the centroid:
+ * streams, dictionaries and the outlier decisions are reproducible bit for bit, a
+ * centroid could in principle differ in its last bit between calls (not observed).
+ * Errors as for the other entry points.
  * ------------------------------------------------------------------------- */
 typedef struct {
     double mean;          /* fitted mean                                   */
