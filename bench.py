@@ -29,7 +29,7 @@ sys.path.insert(0, ROOT)
 # only while the kernel sources still hash to the value recorded with the counters.
 TRAFFIC = {
     "gemm": {"files": ("gemm_wide.hip", "weight_loader.hpp", "sti_internal.hpp"),
-             "sha256": "6aed4c4cc8a6ccb0d121501f66dedd16171ec541c5a94a964e8a76fd7ade36ae",
+             "sha256": "9238ab984c8fdec00c67f3469ef9a4d489dcc60756a097033df6c17f315d0d52",
              "bytes_per_launch": 53694859},
     "decode": {"files": ("decode.hip", "weight_loader.hpp", "sti_internal.hpp"),
                "sha256": "5641b21d214c8b26e119466570da48a993fabee4dd85062a1732f3c96217292f",

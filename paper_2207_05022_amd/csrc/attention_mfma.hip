@@ -16,6 +16,7 @@
 // Profiling"): with key_lengths, sequence b attends to its first key_lengths[b] positions only
 // (clamped to 1..L); rows of padded positions are still computed, from those keys.
 #include "sti_internal.hpp"
+#include "attention_core.hpp"
 
 namespace sti {
 namespace {
@@ -141,44 +142,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attention_mfma_kernel(const _Float
         }
     };
     if constexpr (SHORT > 0) {
-        float16v sc[SHORT];
-        float mx = -INFINITY;
-#pragma unroll
-        for (int kb = 0; kb < SHORT; ++kb) {
-            if (kb >= nkb) break;
-#pragma unroll
-            for (int v = 0; v < 16; ++v) sc[kb][v] = 0.f;
-#pragma unroll
-            for (int s = 0; s < 4; ++s) {
-                half8 kf = *(const half8 *)(Ks + (size_t)(kb * 32 + lr) * KPAD + s * 16 + g * 8);
-                sc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf, qf[s], sc[kb], 0, 0, 0);
-            }
-            if (kb * 32 + 32 > Lk) {   // keys past Lk sit in the last block only
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int key = kb * 32 + (v >> 2) * 8 + g * 4 + (v & 3);
-                    sc[kb][v] = (key < Lk) ? sc[kb][v] : -INFINITY;
-                }
-            }
-#pragma unroll
-            for (int v = 0; v < 16; ++v) mx = fmaxf(mx, sc[kb][v]);
-        }
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        const float shift = -mx * scale;   // (scale > 0: the maximum of the scaled scores)
-#pragma unroll
-        for (int kb = 0; kb < SHORT; ++kb) {
-            if (kb >= nkb) break;
-            uint32_t pk[8];
-#pragma unroll
-            for (int v = 0; v < 16; v += 2) {
-                const float p0 = __builtin_amdgcn_exp2f(fmaf(sc[kb][v], scale, shift));
-                const float p1 = __builtin_amdgcn_exp2f(fmaf(sc[kb][v + 1], scale, shift));
-                run_sum += p0 + p1;
-                pk[v / 2] = (uint32_t)__builtin_bit_cast(uint16_t, (_Float16)p0) |
-                            ((uint32_t)__builtin_bit_cast(uint16_t, (_Float16)p1) << 16);
-            }
-            add_pv(kb, pk);
-        }
+        run_sum = attention_scores_in_registers<SHORT>(qf, Ks, KPAD, Vt, vts, Lk, lane, o);
     } else
     for (int kb = 0; kb < nkb; ++kb) {
         float16v s_acc;
@@ -220,7 +184,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attention_mfma_kernel(const _Float
             for (int v = 0; v < 16; ++v) o[e][v] *= alpha;
         add_pv(kb, pk);
     }
-    run_sum += __shfl_xor(run_sum, 32, 64);
+    if constexpr (SHORT == 0) run_sum += __shfl_xor(run_sum, 32, 64);   // (the register-resident variant returns the pair's sum)
     if (q >= L) return;
     const float inv = 1.0f / run_sum;
     _Float16 *out = ctx + ((int64_t)b * L + q) * ((int64_t)m * DH) + (int64_t)p * DH;

@@ -27,6 +27,7 @@
 // heads' attention itself (kind GEMM_QKV_ATTN): no Q/K/V buffer in memory and no attention launch.
 #include "sti_internal.hpp"
 #include "weight_loader.hpp"
+#include "attention_core.hpp"
 
 namespace sti {
 namespace {
@@ -100,7 +101,6 @@ __global__ __launch_bounds__(NW * KS * 64, 3) void gemm_wide_kernel(
     constexpr int FETCHES = BM / 8;             // fetch instructions per A stage: 8 rows (1 KiB) each
     constexpr int FPW = (FETCHES + NW - 1) / NW;   // per wave: wave w issues fetches w, w + NW, ...
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
-    _Float16 *a_lds = (_Float16 *)smem_raw;
 
     const int N = n_split ? hot_n_blocks * hot_block_rows : hot_block_rows;
     const int K = n_split ? hot_block_cols : hot_n_blocks * hot_block_cols;
@@ -362,66 +362,8 @@ __global__ __launch_bounds__(NW * KS * 64, 3) void gemm_wide_kernel(
         half8 qf[4];
 #pragma unroll
         for (int s = 0; s < 4; ++s) qf[s] = *(const half8 *)(Qs + qrow * ATT_KPAD + s * 16 + g * 8);
-        const float scale = 0.125f * 1.44269504088896340736f;   // 1/sqrt(64) * log2(e)
-        const int nkb = (Lk + 31) / 32;
-        float16v sc[4];
-        float mx = -INFINITY;
-#pragma unroll
-        for (int kb = 0; kb < 4; ++kb) {
-            if (kb >= nkb) break;
-#pragma unroll
-            for (int v = 0; v < 16; ++v) sc[kb][v] = 0.f;
-#pragma unroll
-            for (int s = 0; s < 4; ++s) {
-                const half8 kf = *(const half8 *)(Ks + (kb * 32 + lr) * ATT_KPAD + s * 16 + g * 8);
-                sc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf, qf[s], sc[kb], 0, 0, 0);
-            }
-            if (kb * 32 + 32 > Lk) {   // keys past Lk sit in the last block only
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int key = kb * 32 + (v >> 2) * 8 + g * 4 + (v & 3);
-                    sc[kb][v] = (key < Lk) ? sc[kb][v] : -INFINITY;
-                }
-            }
-#pragma unroll
-            for (int v = 0; v < 16; ++v) mx = fmaxf(mx, sc[kb][v]);
-        }
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        const float shift = -mx * scale;
-        float run_sum = 0.f;
         float16v ov[2];
-#pragma unroll
-        for (int e = 0; e < 2; ++e)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) ov[e][v] = 0.f;
-#pragma unroll
-        for (int kb = 0; kb < 4; ++kb) {
-            if (kb >= nkb) break;
-            uint32_t pk[8];
-#pragma unroll
-            for (int v = 0; v < 16; v += 2) {
-                const float p0 = __builtin_amdgcn_exp2f(fmaf(sc[kb][v], scale, shift));
-                const float p1 = __builtin_amdgcn_exp2f(fmaf(sc[kb][v + 1], scale, shift));
-                run_sum += p0 + p1;
-                pk[v / 2] = (uint32_t)__builtin_bit_cast(uint16_t, (_Float16)p0) |
-                            ((uint32_t)__builtin_bit_cast(uint16_t, (_Float16)p1) << 16);
-            }
-#pragma unroll
-            for (int s2 = 0; s2 < 2; ++s2) {
-                const u32x4 pv = {pk[4 * s2], pk[4 * s2 + 1], pk[4 * s2 + 2], pk[4 * s2 + 3]};
-                const half8 pf = __builtin_bit_cast(half8, pv);
-                const int key0 = kb * 32 + (2 * s2) * 8 + g * 4;
-#pragma unroll
-                for (int e = 0; e < 2; ++e) {
-                    const _Float16 *vrow = Vt + (e * 32 + lr) * ATT_VTS + key0;
-                    const u32x2 lo = *(const u32x2 *)vrow;
-                    const u32x2 hi = *(const u32x2 *)(vrow + 8);
-                    const u32x4 vv = {lo.x, lo.y, hi.x, hi.y};
-                    ov[e] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8, vv), pf, ov[e], 0, 0, 0);
-                }
-            }
-        }
-        run_sum += __shfl_xor(run_sum, 32, 64);
+        const float run_sum = attention_scores_in_registers<4>(qf, Ks, ATT_KPAD, Vt, ATT_VTS, Lk, lane, ov);
         const float inv = 1.0f / run_sum;
         _Float16 *out = (_Float16 *)p.C + (int64_t)(m0 + qrow) * p.ldc + head * ATT_DH;
 #pragma unroll
