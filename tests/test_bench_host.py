@@ -8,6 +8,8 @@ import sys
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 sys.path.insert(0, ROOT)
 
+import numpy as np     # noqa: E402
+
 import bench           # noqa: E402
 import sti_synth as S  # noqa: E402
 
@@ -41,3 +43,25 @@ def test_more_than_one_gpu_is_refused():
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
     assert r.returncode != 0
     assert "one GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_parity_measures_agree_with_the_test_helper():
+    """bench.py states the same two measures the GPU tests assert (tests/parity.py), and they see
+    what they are meant to see: a small element far off in relative terms, a non-finite value."""
+    from parity import parity
+    rng = np.random.default_rng(3)
+    want = rng.normal(0, 1, (4, 50, 64))
+    got = want + rng.normal(0, 1e-3, want.shape)
+    a, b = bench.parity(got, want, 2e-2), parity(got, want, 2e-2)
+    assert a["max_rel_err"] == b["max_rel"] and a["elementwise_violations"] == b["violations"] == 0.0
+    i = np.unravel_index(np.argmin(np.abs(want)), want.shape)
+    got[i] = want[i] + 0.05          # tiny next to the tensor's maximum, large next to rms and to the element
+    a = bench.parity(got, want, 2e-2)
+    assert a["max_rel_err"] < 2e-2 and a["elementwise_violations"] == 1.0 / want.size
+    got[i] = np.nan
+    assert bench.parity(got, want, 2e-2)["elementwise_violations"] == 1.0 / want.size
+
+
+def test_packed_bytes_of_configuration_0():
+    # 12 shards at 4 bits: 12 * 589824 / 2 bytes of indexes + 12 codebooks of 16 float32
+    assert bench.packed_bytes(S.config0()) == 12 * 294912 + 12 * 64
