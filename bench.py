@@ -354,6 +354,66 @@ def bench_ceilings(torch, steps):
     return out
 
 
+PHASES = ("start-up: entry -> first two K tiles requested", "start-up: -> first K tile landed", "K loop",
+          "epilogue arithmetic (Q/K/V tile into LDS for the fused kind)", "stores acknowledged (attention + stores for the fused kind)")
+GEMM_KINDS = {4: "gemm_qkv_attention", 2: "gemm_out", 1: "gemm_ffn_up", 3: "gemm_ffn_down"}
+
+
+def phase_budget_child():
+    """Runs in a process of its own with STI_LIBRARY = libsti_phases.so: configuration 4 through
+    sti_model_forward, then the clock stamps that wave 0 of every workgroup of the last launch of
+    each projection kind left (see STI_PHASE_STAMPS in csrc/gemm_wide.hip)."""
+    import ctypes as C
+    import numpy as np
+    import torch
+    import paper_2207_05022_amd as P
+    from paper_2207_05022_amd import device as D
+    import sti_synth as S
+    wl = S.config4()
+    prec = P.STI_PREC_F16_MFMA
+    shards, params, x = D.upload_workload(wl)
+    store = P.binding.make_store(D.store_from_plan(shards))
+    y = torch.empty_like(x)
+    ws = torch.empty(P.sti_model_workspace_bytes(wl.dims, wl.n_layers, wl.batch, wl.seq, prec), dtype=torch.uint8, device="cuda")
+    for _ in range(3):
+        P.sti_model_forward(wl.dims, store, params, wl.plan, x, y, prec, ws)
+    torch.cuda.synchronize()
+    buf = np.zeros((5, 512, 8), dtype=np.uint64)
+    P.lib.sti_phase_stamps_read.argtypes = [C.c_void_p, C.c_int]
+    rc = P.lib.sti_phase_stamps_read(buf.ctypes.data, 0)
+    assert rc == 0, rc
+    out = {}
+    for kind, name in GEMM_KINDS.items():
+        b = buf[kind].astype(np.int64)
+        b = b[b[:, 0] != 0]
+        if not len(b):
+            continue
+        d = np.diff(b[:, :6], axis=1)                     # clocks per phase, per workgroup
+        wall_us = (b[:, 7] - b[:, 6]) / 100.0             # the wall clock runs at 100 MHz
+        total = b[:, 5] - b[:, 0]
+        out[name] = {
+            "workgroups": int(len(b)),
+            "clocks_per_phase_median": {PHASES[i]: int(np.median(d[:, i])) for i in range(5)},
+            "clocks_per_phase_p90": [int(np.percentile(d[:, i], 90)) for i in range(5)],
+            "clocks_entry_to_exit_median": int(np.median(total)),
+            "clock_ticks_per_us": round(float(np.median(total / np.maximum(wall_us, 1e-9))), 1),
+            "us_entry_to_exit_median": round(float(np.median(wall_us)), 2),
+            "us_first_entry_to_last_exit": round(float((b[:, 7].max() - b[:, 6].min()) / 100.0), 2),
+            "us_entry_after_first_entry_p90": round(float(np.percentile(b[:, 6] - b[:, 6].min(), 90) / 100.0), 2),
+        }
+    print(json.dumps(out))
+
+
+def bench_phase_budget():
+    import subprocess
+    env = dict(os.environ, STI_LIBRARY=os.path.join(ROOT, "paper_2207_05022_amd", "libsti_phases.so"))
+    r = subprocess.run([sys.executable, os.path.abspath(__file__), "--phase-budget-child"], env=env,
+                       capture_output=True, text=True, timeout=300)
+    if r.returncode != 0:
+        raise RuntimeError(f"phase budget run failed ({r.returncode}): {r.stderr[-2000:]}")
+    return json.loads(r.stdout.strip().split("\n")[-1])
+
+
 def cpu_baselines(S, wl, y, ds):
     """The oracle as it stands, on a bounded sample of both workloads; its output for the model
     workload is also what the output `y` of the timed calls is compared with."""
@@ -396,6 +456,10 @@ def main():
     ap.add_argument("--ceilings", action="store_true",
                     help="also run the ceiling probes: an MFMA-only loop, HBM streams with the read : write mix of "
                          "decompression, and the vendor GEMM library on configuration 4's projection shapes")
+    ap.add_argument("--phase-budget", action="store_true",
+                    help="also run configuration 4 on the build whose many-token GEMM kernel records clock stamps "
+                         "(libsti_phases.so, in a process of its own) and report the clocks per kernel phase")
+    ap.add_argument("--phase-budget-child", action="store_true", help=argparse.SUPPRESS)
     ap.add_argument("--quantize", action="store_true",
                     help="also time the outlier-aware quantizer on one BERT-base layer")
     args = ap.parse_args()
@@ -410,6 +474,9 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py needs a GPU (no CPU fallback exists)", file=sys.stderr)
         sys.exit(2)
+    if args.phase_budget_child:
+        phase_budget_child()
+        return
     import paper_2207_05022_amd as P
     from paper_2207_05022_amd import device as D
     import sti_synth as S
@@ -442,6 +509,8 @@ def main():
         line["few_token"] = bench_few_token(P, D, torch, S, args.steps, args.warmup, not args.no_cpu_baseline)
     if args.ceilings:
         line["ceilings"] = bench_ceilings(torch, args.steps)
+    if args.phase_budget:
+        line["phase_budget"] = bench_phase_budget()
     if args.quantize:
         line["quantizer"] = bench_quantizer(P, torch, S, args.steps, args.warmup)
     if not args.no_cpu_baseline:

@@ -11,7 +11,9 @@ import os
 from typing import Optional, Sequence
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(HERE, "libsti.so")
+# STI_LIBRARY names another build of the same sources to load instead (the build with phase time
+# stamps that bench.py --phase-budget measures with); unset, the product library beside this file
+LIB_PATH = os.environ.get("STI_LIBRARY") or os.path.join(HERE, "libsti.so")
 
 STI_F32, STI_F16, STI_BF16 = 0, 1, 2
 STI_PREC_F32, STI_PREC_F16_MFMA = 0, 1

@@ -13,6 +13,9 @@ OBJ_DIR = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libsti.so")
 PROBES_SRC = os.path.join(CSRC, "probes", "ceilings.hip")
 PROBES_LIB = os.path.join(HERE, "libsti_probes.so")   # ceiling probes for bench.py --ceilings, not part of libsti
+# libsti with the many-token GEMM kernel compiled to record its phase time stamps (bench.py --phase-budget)
+PHASES_SRC = os.path.join(CSRC, "gemm_wide.hip")
+PHASES_LIB = os.path.join(HERE, "libsti_phases.so")
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
@@ -47,10 +50,17 @@ def build(verbose: bool = False) -> str:
                        check=True, stderr=subprocess.PIPE, text=True)
         subprocess.run([HIPCC, *FLAGS, "-shared", PROBES_SRC, "-o", PROBES_LIB],
                        check=True, stderr=subprocess.PIPE, text=True)
+        stamped = os.path.join(OBJ_DIR, "gemm_wide_phases.o")
+        subprocess.run([HIPCC, *FLAGS, "-DSTI_PHASE_STAMPS", "-c", PHASES_SRC, "-o", stamped],
+                       check=True, stderr=subprocess.PIPE, text=True)
+        plain = os.path.join(OBJ_DIR, "gemm_wide.o")
+        subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", PHASES_LIB,
+                        *[stamped if o == plain else o for o in objs]],
+                       check=True, stderr=subprocess.PIPE, text=True)
     except subprocess.CalledProcessError as err:
         raise RuntimeError(f"hipcc failed: {' '.join(err.cmd)}\n{err.stderr}") from None
     if verbose:
-        print(f"built {LIB} from {len(srcs)} sources and {PROBES_LIB}")
+        print(f"built {LIB} from {len(srcs)} sources, {PROBES_LIB} and {PHASES_LIB}")
     return LIB
 
 

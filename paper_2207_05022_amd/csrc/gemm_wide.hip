@@ -29,6 +29,45 @@
 #include "weight_loader.hpp"
 #include "attention_core.hpp"
 
+// STI_PHASE_STAMPS (the phase-budget build libsti_phases.so only, never the product library): wave 0
+// of every workgroup reads the shader clock counter at six points (kernel entry, prologue loads
+// requested, first K tile landed, K loop done, epilogue arithmetic done, last store acknowledged)
+// plus the 100 MHz wall clock at both ends, keeps the values in scalar registers (a store inside the
+// K loop would count against its hand-written waits) and writes them once, at its exit.
+#ifdef STI_PHASE_STAMPS
+namespace {
+constexpr int kStampKinds = 5, kStampSlots = 512, kStampWords = 8;
+__device__ unsigned long long sti_phase_stamps[kStampKinds * kStampSlots * kStampWords];
+}
+// out: [kind][slot][8] = six clock stamps, wall clock at entry, wall clock at exit (0 = slot unused)
+extern "C" int sti_phase_stamps_read(unsigned long long *out, int clear)
+{
+    hipError_t e = hipMemcpyFromSymbol(out, HIP_SYMBOL(sti_phase_stamps), sizeof(sti_phase_stamps));
+    if (e == hipSuccess && clear) {
+        void *dev = nullptr;
+        e = hipGetSymbolAddress(&dev, HIP_SYMBOL(sti_phase_stamps));
+        if (e == hipSuccess) e = hipMemset(dev, 0, sizeof(sti_phase_stamps));
+    }
+    return (int)e;
+}
+#define STI_STAMP(i) (stamp[i] = __builtin_amdgcn_s_memtime())
+#define STI_STAMPS_OUT()                                                                               \
+    do {                                                                                               \
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");                                               \
+        STI_STAMP(5);                                                                                  \
+        const unsigned slot = blockIdx.y * gridDim.x + blockIdx.x;                                     \
+        if (threadIdx.x == 0 && slot < (unsigned)kStampSlots) {                                        \
+            unsigned long long *o = sti_phase_stamps + ((size_t)KIND * kStampSlots + slot) * kStampWords; \
+            for (int i_ = 0; i_ < 6; ++i_) o[i_] = stamp[i_];                                          \
+            o[6] = wall0;                                                                              \
+            o[7] = wall_clock64();                                                                     \
+        }                                                                                              \
+    } while (0)
+#else
+#define STI_STAMP(i) ((void)0)
+#define STI_STAMPS_OUT() ((void)0)
+#endif
+
 namespace sti {
 namespace {
 
@@ -89,10 +128,18 @@ __global__ __launch_bounds__(NW * KS * 64, 3) void gemm_wide_kernel(
     // what the first loads of a workgroup depend on, as leading scalar arguments: these arrive
     // preloaded in scalar registers (the build asks for kernel-argument preloading), so that the
     // first A fetches and weight loads are not behind a round trip to the argument buffer
-    const void *hot_A, const void *hot_w0, int64_t hot_w_stride, int32_t hot_T, int32_t hot_lda,
-    int32_t hot_n_blocks, int32_t hot_block_rows, int32_t hot_block_cols, int32_t hot_k_splits,
+    // (14 dwords fit: block_shape = block_rows | block_cols << 16, blocks_splits = n_blocks | k_splits << 16)
+    const void *hot_A, const void *hot_w0, const void *hot_resid, const float *hot_bias0, int32_t hot_w_stride,
+    int32_t hot_T, int32_t hot_lda, int32_t hot_ldr, uint32_t hot_block_shape, uint32_t hot_blocks_splits,
     GemmProblem p, GemmBlocks blocks)   // (of p, only the fields that are not among the leading arguments are read)
 {
+    const int hot_block_rows = hot_block_shape & 0xffff, hot_block_cols = hot_block_shape >> 16;
+    const int hot_n_blocks = hot_blocks_splits & 0xffff, hot_k_splits = hot_blocks_splits >> 16;
+#ifdef STI_PHASE_STAMPS
+    unsigned long long stamp[6] = {0, 0, 0, 0, 0, 0};
+    const unsigned long long wall0 = wall_clock64();
+    STI_STAMP(0);
+#endif
     constexpr int BM = RA * 32, BN = NW * 32, NT = NW * KS * 64, NTH = NW * 64;
     constexpr bool n_split = (KIND == GEMM_QKV || KIND == GEMM_FFN_UP || KIND == GEMM_QKV_ATTN);
     constexpr bool qkv = (KIND == GEMM_QKV || KIND == GEMM_QKV_ATTN);
@@ -193,7 +240,7 @@ __global__ __launch_bounds__(NW * KS * 64, 3) void gemm_wide_kernel(
             blk = kt / tiles_per_kblock; ktb = kt - blk * tiles_per_kblock; row = nw;
         }
         // (the blocks of a working buffer lie at a constant distance: no look-up in the block table)
-        const uint8_t *base = (const uint8_t *)hot_w0 + (int64_t)blk * hot_w_stride;
+        const uint8_t *base = (const uint8_t *)hot_w0 + (int64_t)blk * hot_w_stride;   // (stride < 2^31)
         return base + tiled_cell_offset(row >> 5, ktb, hot_block_cols);   // wave-uniform
     };
 
@@ -224,7 +271,7 @@ __global__ __launch_bounds__(NW * KS * 64, 3) void gemm_wide_kernel(
     // covers them.  (A variant of its own: with K split over workgroups nothing is added here.)
     constexpr bool PRE = EARLY;
     static_assert(!EARLY || (!n_split && RA <= 2), "early operands: 64-row tiles of OUT / FFN_DOWN");
-    const _Float16 *R = (const _Float16 *)p.resid;
+    const _Float16 *R = (const _Float16 *)hot_resid;
     f32x4 bias[2][2];
     u32x4 resv[PRE ? RA : 1][2];
     auto load_epilogue_operands = [&]() {
@@ -235,11 +282,11 @@ __global__ __launch_bounds__(NW * KS * 64, 3) void gemm_wide_kernel(
             if constexpr (qkv) {
                 const int nrow = nrow0 + c;
                 const int which = nrow / p.d_head, e0 = nrow - which * p.d_head;
-                bp = (which == 0 ? p.bias0 : (which == 1 ? p.bias1 : p.bias2)) + blocks.b[nblk].shard * p.d_head + e0;
+                bp = (which == 0 ? hot_bias0 : (which == 1 ? p.bias1 : p.bias2)) + blocks.b[nblk].shard * p.d_head + e0;
             } else if constexpr (KIND == GEMM_FFN_UP) {
-                bp = p.bias0 + blocks.b[nblk].shard * hot_block_rows + nrow0 + c;
+                bp = hot_bias0 + blocks.b[nblk].shard * hot_block_rows + nrow0 + c;
             } else {
-                bp = p.bias0 + nw + c;
+                bp = hot_bias0 + nw + c;
             }
             bias[q][0] = *(const f32x4 *)bp;
             bias[q][1] = *(const f32x4 *)(bp + 4);
@@ -247,13 +294,9 @@ __global__ __launch_bounds__(NW * KS * 64, 3) void gemm_wide_kernel(
         if constexpr (PRE) {
 #pragma unroll
             for (int i = 0; i < RA; ++i) {
-                const int m = m0 + i * 32 + lr;
+                const int m = min(m0 + i * 32 + lr, hot_T - 1);   // (rows past T: row T-1 again, never stored)
 #pragma unroll
-                for (int q = 0; q < 2; ++q) {
-                    u32x4 v = {0, 0, 0, 0};
-                    if (m < hot_T) v = *(const u32x4 *)(R + (int64_t)m * p.ldr + nw + 16 * q + 8 * g);
-                    resv[i][q] = v;
-                }
+                for (int q = 0; q < 2; ++q) resv[i][q] = *(const u32x4 *)(R + (int64_t)m * hot_ldr + nw + 16 * q + 8 * g);
             }
         }
     };
@@ -271,6 +314,9 @@ __global__ __launch_bounds__(NW * KS * 64, 3) void gemm_wide_kernel(
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
         __builtin_amdgcn_sched_barrier(0);
+#ifdef STI_PHASE_STAMPS
+        if (kt == 0) STI_STAMP(2);
+#endif
         if (KS == 2 && kt + 2 < nkt) issue(kt + 2, bnew);
         const unsigned char *stage = smem_raw + (half * 3 + kt % 3) * (STAGE * 2);
         half8 a_cur[RA], a_nxt[RA];
@@ -301,12 +347,14 @@ __global__ __launch_bounds__(NW * KS * 64, 3) void gemm_wide_kernel(
     if (PRE && half == 0) load_epilogue_operands();
     if (nkt > 0) issue(0, bw[0]);
     if (nkt > 1) issue(1, bw[1]);
+    STI_STAMP(1);
     for (int kt = 0; kt < nkt; kt += 3) {
         step(kt, bw[0], bw[2]);
         if (kt + 1 < nkt) step(kt + 1, bw[1], bw[0]);
         if (kt + 2 < nkt) step(kt + 2, bw[2], bw[1]);
     }
 #undef STI_WAIT_LOADS
+    STI_STAMP(3);
 
     // ---- epilogue ----
     // Lane l holds token row lr and output columns (v/4)*8 + g*4 + v%4 of each 32 x 32 block.
@@ -352,6 +400,7 @@ __global__ __launch_bounds__(NW * KS * 64, 3) void gemm_wide_kernel(
             }
         }
         __syncthreads();
+        STI_STAMP(4);   // (here: Q, K, V of the tile are in LDS; what follows is the attention)
         const int head = tile_n * 2 + (wave >> 2);          // present-head index of waves 0..7
         if (wave >= 8 || head >= hot_n_blocks) return;
         hb = (_Float16 *)smem_raw + (wave >> 2) * ATT_HEAD_HALVES;
@@ -375,6 +424,7 @@ __global__ __launch_bounds__(NW * KS * 64, 3) void gemm_wide_kernel(
                 for (int i = 0; i < 4; ++i) h[i] = (_Float16)(ov[e][v4 * 4 + i] * inv);
                 *(half4 *)(out + e * 32 + v4 * 8 + g * 4) = h;
             }
+        STI_STAMPS_OUT();
         return;
     }
     if constexpr (KS == 2) {
@@ -423,6 +473,8 @@ __global__ __launch_bounds__(NW * KS * 64, 3) void gemm_wide_kernel(
                 }
             }
         }
+        STI_STAMP(4);
+        STI_STAMPS_OUT();
         return;
     }
     if (half == 0) {
@@ -438,7 +490,7 @@ __global__ __launch_bounds__(NW * KS * 64, 3) void gemm_wide_kernel(
 #pragma unroll
             for (int q = 0; q < 2; ++q) {
                 u32x4 v = {0, 0, 0, 0};
-                if (m < hot_T) v = *(const u32x4 *)(R + (int64_t)m * p.ldr + nw + 16 * q + 8 * g);
+                if (m < hot_T) v = *(const u32x4 *)(R + (int64_t)m * hot_ldr + nw + 16 * q + 8 * g);
                 res[q] = __builtin_bit_cast(half8, v);
             }
         }
@@ -468,6 +520,7 @@ __global__ __launch_bounds__(NW * KS * 64, 3) void gemm_wide_kernel(
     }
     }
     __syncthreads();
+    STI_STAMP(4);
     // BN/8 lanes per tile row: every store instruction writes whole rows of the tile
     _Float16 *C = (_Float16 *)p.C;
     constexpr int PIECES_PER_ROW = BN / 8;
@@ -485,6 +538,7 @@ __global__ __launch_bounds__(NW * KS * 64, 3) void gemm_wide_kernel(
         const int m = m0 + pc / PIECES_PER_ROW, n = tile_n * BN + (pc % PIECES_PER_ROW) * 8;
         if (m < hot_T && n < N) *(u32x4 *)(C + (int64_t)m * p.ldc + n) = piece[j];
     }
+    STI_STAMPS_OUT();
 }
 
 template <int KIND, int RA, int NW, int KS, bool EARLY>
@@ -516,7 +570,8 @@ hipError_t launch_variant(const GemmProblem &p, const GemmBlocks &blocks, int N,
     dim3 grid(((total + 7) / 8) * 8, (!n_split && p.k_splits > 1) ? p.k_splits : 1);
     const int64_t w_stride = p.n_blocks > 1 ? (const uint8_t *)blocks.b[1].w - (const uint8_t *)blocks.b[0].w : 0;
     launch((gemm_wide_kernel<KIND, RA, NW, KS, EARLY>), grid, dim3(NW * KS * 64), lds, stream, p.A, blocks.b[0].w,
-           w_stride, p.T, p.lda, p.n_blocks, p.block_rows, p.block_cols, p.k_splits, p, blocks);
+           p.resid, p.bias0, (int32_t)w_stride, p.T, p.lda, p.ldr, (uint32_t)p.block_rows | (uint32_t)p.block_cols << 16,
+           (uint32_t)p.n_blocks | (uint32_t)(p.k_splits > 1 ? p.k_splits : 1) << 16, p, blocks);
     return hipGetLastError();
 }
 
@@ -555,6 +610,10 @@ bool gemm_wide_supported(const GemmProblem &p, const GemmBlocks &blocks)
     const int64_t stride = p.n_blocks > 1 ? (const uint8_t *)blocks.b[1].w - (const uint8_t *)blocks.b[0].w : 0;
     for (int b = 2; b < p.n_blocks; ++b)
         if ((const uint8_t *)blocks.b[b].w - (const uint8_t *)blocks.b[0].w != stride * b) return false;
+    // ... and takes the stride and the block shape and count as 32- and 16-bit kernel arguments
+    if (stride < 0 || stride > INT32_MAX || p.n_blocks > 0xffff || p.block_rows > 0xffff || p.block_cols > 0xffff ||
+        p.k_splits > 0xffff)
+        return false;
     return true;
 }
 
