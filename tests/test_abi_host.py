@@ -38,6 +38,17 @@ def test_every_declared_symbol_is_exported(P):
         assert hasattr(P.lib, n), n
 
 
+def test_phase_stamp_build_exports_the_same_boundary(P):
+    """libsti_phases.so (bench.py --phase-budget loads it through STI_LIBRARY) is the library with
+    clock stamps compiled into one kernel: same boundary, plus the call that reads the stamps,
+    which the product library does not have."""
+    import ctypes as C
+    L = C.CDLL(os.path.join(ROOT, "paper_2207_05022_amd", "libsti_phases.so"))
+    for n in declared_functions():
+        assert hasattr(L, n), n
+    assert hasattr(L, "sti_phase_stamps_read") and not hasattr(P.lib, "sti_phase_stamps_read")
+
+
 def test_status_strings(P):
     seen = {P.status_string(i) for i in range(10)}
     assert len(seen) == 10 and "ok" in seen
