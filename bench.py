@@ -346,10 +346,27 @@ def bench_ceilings(torch, steps):
         us = e0.elapsed_time(e1) / reps * 1e3
         vendor[name] = {"us_per_call": round(us, 2), "TFLOP/s": round(2.0 * M * N * K / us / 1e6, 1),
                         "frac_of_published_peak": round(2.0 * M * N * K / us / 1e6 / MFMA_F16_PEAK_TFLOPS, 4)}
+    # the same call on all-zero operands: how much of the time is the clock the chip holds under
+    # switching activity (its shader clock is data dependent), not the kernel
+    a = torch.zeros(4096, 768, device="cuda", dtype=torch.float16)
+    w = torch.zeros(3072, 768, device="cuda", dtype=torch.float16)
+    b = torch.zeros(3072, device="cuda", dtype=torch.float16)
+    for _ in range(5):
+        torch.nn.functional.linear(a, w, b)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    reps = max(20, steps * 5)
+    e0.record()
+    for _ in range(reps):
+        torch.nn.functional.linear(a, w, b)
+    e1.record()
+    torch.cuda.synchronize()
+    zero_us = e0.elapsed_time(e1) / reps * 1e3
     flops = sum(2.0 * 4096 * n * k for n, k in ((2304, 768), (768, 768), (3072, 768), (768, 3072)))
     us = sum(v["us_per_call"] for v in vendor.values())
     vendor["mean_of_the_four"] = {"us_per_call": round(us / 4, 2), "TFLOP/s": round(flops / us / 1e6, 1),
                                   "frac_of_published_peak": round(flops / us / 1e6 / MFMA_F16_PEAK_TFLOPS, 4)}
+    vendor["gemm_ffn_up_all_zero_operands"] = {"us_per_call": round(zero_us, 2),
+                                               "speedup_over_random_operands": round(vendor["gemm_ffn_up"]["us_per_call"] / zero_us, 3)}
     out["vendor_gemm_library_same_shapes"] = vendor
     return out
 
