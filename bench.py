@@ -302,7 +302,7 @@ def bench_ceilings(torch, steps):
     GEMM + bias without GELU or residual; a reference point, not part of the path)."""
     import ctypes as C
     lib = C.CDLL(os.path.join(ROOT, "paper_2207_05022_amd", "libsti_probes.so"))
-    lib.sti_probe_mfma.argtypes = [C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p,
+    lib.sti_probe_mfma.argtypes = [C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p,
                                    C.POINTER(C.c_double), C.POINTER(C.c_double)]
     lib.sti_probe_stream.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64, C.c_int, C.c_int, C.c_void_p,
                                      C.POINTER(C.c_double), C.POINTER(C.c_double)]
@@ -311,11 +311,11 @@ def bench_ceilings(torch, steps):
     scratch = torch.empty(256 * 768, dtype=torch.float32, device="cuda")
     ms, work = C.c_double(), C.c_double()
     cus = torch.cuda.get_device_properties(0).multi_processor_count
-    for waves in (4, 12):
-        rc = lib.sti_probe_mfma(cus, waves, 3000, 5, scratch.data_ptr(), stream, C.byref(ms), C.byref(work))
+    for waves, varied in ((4, 0), (12, 0), (12, 1)):
+        rc = lib.sti_probe_mfma(cus, waves, 3000, 5, varied, scratch.data_ptr(), stream, C.byref(ms), C.byref(work))
         assert rc == 0, rc
         tflops = work.value / (ms.value * 1e-3) / 1e12
-        out[f"mfma_only_loop_{waves}_waves_per_cu"] = {
+        out[f"mfma_only_loop_{waves}_waves_per_cu" + ("_varied_random_operands" if varied else "")] = {
             "TFLOP/s": round(tflops, 1), "frac_of_published_peak": round(tflops / MFMA_F16_PEAK_TFLOPS, 4),
             "implied_clock_GHz": round(tflops * 1e12 / (cus * 4096.0) / 1e9, 3), "ms_per_launch": round(ms.value, 4)}
     n_in = 1 << 26

@@ -4,6 +4,9 @@
 //
 //   sti_probe_mfma    a loop of v_mfma_f32_32x32x16_f16 on register operands only (no memory, no LDS,
 //                     no barriers): the matrix-core rate at the clock the chip holds under that load.
+//                     `varied` = 0: the same two operand registers in every MFMA; 1: four pseudo-random
+//                     operand pairs of unit scale taken in turn (the clock the chip holds depends on how
+//                     much the operands change from one instruction to the next).
 //   sti_probe_stream  every thread reads 16 bytes and writes `ratio` x 16 bytes, coalesced, non-temporal:
 //                     the HBM rate of a stream with the read : write mix of shard decompression
 //                     (1 : 4.64 for the 2..6-bit mix of the decode-only configuration) beside a 1 : 1 copy.
@@ -17,19 +20,30 @@ typedef float float16v __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 // 4 independent accumulators per wave: consecutive MFMAs of a wave never wait for each other
+template <bool VARIED>
 __global__ __launch_bounds__(768) void mfma_loop_kernel(float *out, int iters)
 {
-    half8 a, b;
-    for (int i = 0; i < 8; ++i) {
-        a[i] = (_Float16)(threadIdx.x * 0.001f + i);
-        b[i] = (_Float16)(i * 0.5f);
-    }
+    half8 a[4], b[4];
+    uint32_t h = (blockIdx.x * 768u + threadIdx.x) * 2654435761u + 12345u;
+    for (int j = 0; j < 4; ++j)
+        for (int i = 0; i < 8; ++i) {
+            if (VARIED) {
+                h = h * 1664525u + 1013904223u;
+                a[j][i] = (_Float16)(((int)(h >> 8) & 0xffff) * (4.0f / 65536.0f) - 2.0f);   // uniform in [-2, 2)
+                h = h * 1664525u + 1013904223u;
+                b[j][i] = (_Float16)(((int)(h >> 8) & 0xffff) * (4.0f / 65536.0f) - 2.0f);
+            } else {
+                a[j][i] = (_Float16)(threadIdx.x * 0.001f + i);
+                b[j][i] = (_Float16)(i * 0.5f);
+            }
+        }
     float16v acc[4];
     for (int j = 0; j < 4; ++j)
         for (int v = 0; v < 16; ++v) acc[j][v] = 0.f;
     for (int it = 0; it < iters; ++it) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, acc[j], 0, 0, 0);
+        for (int j = 0; j < 4; ++j)
+            acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[VARIED ? j : 0], b[VARIED ? (j + 1) & 3 : 0], acc[j], 0, 0, 0);
     }
     float s = 0.f;
     for (int j = 0; j < 4; ++j)
@@ -76,7 +90,7 @@ extern "C" {
 // `blocks` workgroups of `waves` waves (1..12) run `iters` x 4 MFMAs per wave.  scratch: DEVICE,
 // blocks * waves * 64 floats.  Returns 0 and the milliseconds per launch (average of `reps`), and the
 // flops of one launch in *flops.
-int sti_probe_mfma(int blocks, int waves, int iters, int reps, float *scratch, void *hip_stream,
+int sti_probe_mfma(int blocks, int waves, int iters, int reps, int varied, float *scratch, void *hip_stream,
                    double *ms_per_launch, double *flops)
 {
     if (blocks <= 0 || waves <= 0 || waves > 12 || iters <= 0 || reps <= 0 || !scratch || !ms_per_launch || !flops)
@@ -84,7 +98,8 @@ int sti_probe_mfma(int blocks, int waves, int iters, int reps, float *scratch, v
     hipStream_t stream = (hipStream_t)hip_stream;
     *flops = (double)blocks * waves * iters * 4 * (2.0 * 32 * 32 * 16);
     return time_launches(stream, reps, ms_per_launch, [&] {
-        hipLaunchKernelGGL(mfma_loop_kernel, dim3(blocks), dim3(waves * 64), 0, stream, scratch, iters);
+        if (varied) hipLaunchKernelGGL(mfma_loop_kernel<true>, dim3(blocks), dim3(waves * 64), 0, stream, scratch, iters);
+        else hipLaunchKernelGGL(mfma_loop_kernel<false>, dim3(blocks), dim3(waves * 64), 0, stream, scratch, iters);
     });
 }
 
