@@ -299,10 +299,16 @@ static_assert(kSkinnyMaxTokens >= 192, "the partial-sum planes are sized with kS
 
 // One layer, arguments already validated.  `in` is float32 (F32 precision) or
 // binary16 (MFMA precision); `out` is written as out_dtype.
+int spare_decode_workgroups(const sti_dims &d, int B, int Lseq, int m, sti_precision prec)
+{
+    if (prec != STI_PREC_F16_MFMA || m <= 0 || few_token_path(d, (int64_t)B * Lseq)) return 0;
+    return gemm_wide_fuses_attention(B, Lseq, m, d.d_head) ? gemm_wide_spare_workgroups(B, m) : 0;
+}
+
 sti_status run_layer(const sti_dims &d, const sti_shard *shards, const sti_layer_params &prm,
                      const void *in, void *out, sti_dtype out_dtype, int B, int Lseq,
                      sti_precision prec, uint8_t *ws, const WorkspaceLayout &wl, hipStream_t stream,
-                     const void *predecoded, const int32_t *key_lengths)
+                     const void *predecoded, const int32_t *key_lengths, const NextLayerDecode *next)
 {
     const int dm = d.d_model, M = d.n_heads, dh = d.d_head, f = d.ffn_per_shard;
     const int T = B * Lseq;
@@ -418,8 +424,13 @@ sti_status run_layer(const sti_dims &d, const sti_shard *shards, const sti_layer
             // sequences of 128 tokens: the projection's 128-row tiles are whole sequences, and its
             // workgroups go on to the attention of the heads they hold (no Q/K/V buffer)
             p.kind = GEMM_QKV_ATTN; p.C = ctx; p.ldc = m * dh; p.key_lengths = key_lengths;
+            if (next && next->workgroups > 0 && next->n_shards > 0) {
+                p.next_table = next->table; p.next_shards = next->n_shards; p.next_out = next->out;
+                p.next_workgroups = next->workgroups; p.next_ffn_per_shard = f;
+            }
             STI_TRY(gemm(p, bq));
         } else {
+            if (next) return STI_ERR_UNSUPPORTED;   // (the caller asked spare_decode_workgroups first)
             STI_TRY(gemm(p, bq));
             STI_TRY(timed(STI_K_ATTENTION, stream, [&] {
                 return f32 ? launch_attention_f32((const float *)qkv, (float *)ctx, B, Lseq, m, dh, key_lengths, stream)
@@ -860,29 +871,42 @@ sti_status model_forward(const sti_dims *dims, int n_layers, const sti_shard *st
     int decode_group = (int)(((size_t)64 << 20) / (layer_w16_bytes ? layer_w16_bytes : 1));
     if (decode_group < 1) decode_group = 1;
     if (decode_group > n_layers) decode_group = n_layers;
+    const ShardDesc *dev_table = (const ShardDesc *)(ws + wl.table);
+    auto last_shard = [&](int l) { return (l + 1 < n_layers) ? first_shard[l + 1] : table.size(); };
+    // put layer l's outlier dictionaries into its working buffer (absent in most stores)
+    auto patch_layer = [&](int l) -> sti_status {
+        const size_t a = first_shard[l], b = last_shard(l);
+        uint32_t max_outliers = 0;
+        InlineShardTable t;
+        memset(&t, 0, sizeof(t));
+        for (size_t e = a; e < b; ++e) {
+            t.d[e - a] = table[e];
+            if (table[e].n_outliers > max_outliers) max_outliers = table[e].n_outliers;
+        }
+        if (max_outliers > 0)
+            STI_TRY(launch_patch_outliers_tiled(t, (int)(b - a), max_outliers, dims->d_model, dims->d_head,
+                                                dims->ffn_per_shard, ws + wl.w16 + a * wsh * 2, stream));
+        return STI_OK;
+    };
     // decompress layers [l0, l1) into their working buffers and apply their outlier dictionaries
     auto decode_layers = [&](int l0, int l1) -> sti_status {
-        const ShardDesc *dev_table = (const ShardDesc *)(ws + wl.table);
-        const size_t lo = first_shard[l0], hi = (l1 < n_layers) ? first_shard[l1] : table.size();
+        const size_t lo = first_shard[l0], hi = last_shard(l1 - 1);
         if (hi == lo) return STI_OK;
         STI_TRY(timed(STI_K_DECODE, stream, [&] {
             return launch_decode_tiled_table(dev_table + lo, (int)(hi - lo), dims->d_model, dims->d_head,
                                              dims->ffn_per_shard, ws + wl.w16 + lo * wsh * 2, stream);
         }));
-        for (int l = l0; l < l1; ++l) {   // (absent in most stores)
-            const size_t a = first_shard[l], b = (l + 1 < n_layers) ? first_shard[l + 1] : table.size();
-            uint32_t max_outliers = 0;
-            InlineShardTable t;
-            memset(&t, 0, sizeof(t));
-            for (size_t e = a; e < b; ++e) {
-                t.d[e - a] = table[e];
-                if (table[e].n_outliers > max_outliers) max_outliers = table[e].n_outliers;
-            }
-            if (max_outliers > 0)
-                STI_TRY(launch_patch_outliers_tiled(t, (int)(b - a), max_outliers, dims->d_model, dims->d_head,
-                                                    dims->ffn_per_shard, ws + wl.w16 + a * wsh * 2, stream));
+        for (int l = l0; l < l1; ++l) {
+            sti_status ps = patch_layer(l);
+            if (ps != STI_OK) return ps;
         }
         return STI_OK;
+    };
+    // A layer whose Q/K/V projection leaves compute units idle (spare_decode_workgroups) decompresses
+    // the layer behind it on those units: then only the first layer (and whatever follows a layer that
+    // cannot) is decompressed by a launch of its own.
+    auto spare = [&](int l) {
+        return spare_decode_workgroups(*dims, batch, seq, (int)(last_shard(l) - first_shard[l]), precision);
     };
     const sti_dtype act = (precision == STI_PREC_F32) ? STI_F32 : STI_F16;
     const void *cur = x;
@@ -892,17 +916,35 @@ sti_status model_forward(const sti_dims *dims, int n_layers, const sti_shard *st
         cur = ws + wl.act[0];
         next_buf = 1;
     }
+    int decoded_upto = 0;   // layers [0, decoded_upto) have their working buffers (as far as the stream is concerned)
     for (int l = 0; l < n_layers; ++l) {
         const bool last = (l == n_layers - 1);
         void *out = last ? y : (void *)(ws + wl.act[next_buf]);
-        if (whole_model_fits && !table.empty() && l % decode_group == 0) {
-            st = decode_layers(l, l + decode_group < n_layers ? l + decode_group : n_layers);
-            if (st != STI_OK) return st;
+        NextLayerDecode next_decode = {nullptr, 0, nullptr, 0};
+        if (whole_model_fits && !table.empty()) {
+            const int spare_here = spare(l);
+            if (l >= decoded_upto) {
+                int l1 = l + decode_group < n_layers ? l + decode_group : n_layers;
+                if (spare_here > 0) l1 = l + 1;   // the layers behind this one ride along with their predecessors
+                st = decode_layers(l, l1);
+                if (st != STI_OK) return st;
+                decoded_upto = l1;
+            }
+            if (spare_here > 0 && l + 1 == decoded_upto && l + 1 < n_layers) {
+                const size_t a = first_shard[l + 1], b = last_shard(l + 1);
+                if (b > a) next_decode = {dev_table + a, (int)(b - a), ws + wl.w16 + a * wsh * 2, spare_here};
+                decoded_upto = l + 2;
+            }
         }
         const void *predecoded = whole_model_fits ? (const void *)(ws + wl.w16 + first_shard[l] * wsh * 2) : nullptr;
         st = run_layer(*dims, &chosen[(size_t)l * M], params[l], cur, out, last ? io_dtype : act,
-                       batch, seq, precision, ws, wl, stream, predecoded, masked ? key_lengths : nullptr);
+                       batch, seq, precision, ws, wl, stream, predecoded, masked ? key_lengths : nullptr,
+                       next_decode.workgroups > 0 ? &next_decode : nullptr);
         if (st != STI_OK) return st;
+        if (next_decode.workgroups > 0) {
+            st = patch_layer(l + 1);
+            if (st != STI_OK) return st;
+        }
         cur = out;
         next_buf ^= 1;
     }

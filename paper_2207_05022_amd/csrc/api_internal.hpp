@@ -29,13 +29,28 @@ sti_status check_io(const void *x, void *y, sti_dtype io, int64_t T, int d);
 
 // One layer over shards[M] (bitwidth 0 = absent), arguments already validated.  `in` is
 // float32 (F32 precision) or binary16 (MFMA precision); `out` is written as out_dtype.
+// What a layer's fused Q/K/V + attention launch does on the compute units its tiles leave idle:
+// decompress the following layer (n_shards shards of the device table into the working buffer `out`,
+// dictionaries of outliers not applied) with `workgroups` workgroups.
+struct NextLayerDecode {
+    const ShardDesc *table;
+    int n_shards;
+    void *out;
+    int workgroups;
+};
+// Workgroups such a launch has to spare for a layer of m present shards (0: its projection does not
+// take that form, or fills the chip).
+int spare_decode_workgroups(const sti_dims &d, int B, int Lseq, int m, sti_precision prec);
+
 sti_status run_layer(const sti_dims &d, const sti_shard *shards, const sti_layer_params &prm,
                      const void *in, void *out, sti_dtype out_dtype, int B, int Lseq,
                      sti_precision prec, uint8_t *ws, const WorkspaceLayout &wl, hipStream_t stream,
-                     const void *predecoded = nullptr, const int32_t *key_lengths = nullptr);
+                     const void *predecoded = nullptr, const int32_t *key_lengths = nullptr,
+                     const NextLayerDecode *next = nullptr);
 // `predecoded`: the layer's present shards already sit there in fragment-tiled binary16 order
 // (outliers applied); run_layer then decompresses nothing.
 // `key_lengths` (device, [B]): real positions per padded sequence; null = every position is real.
+// `next` (only with `predecoded`, and only when spare_decode_workgroups says so for this layer).
 sti_status check_key_lengths(const int32_t *key_lengths);   // non-null, 4-byte aligned
 
 }  // namespace sti

@@ -153,10 +153,6 @@ __device__ inline void decode_raw_chunk(const float *data, uint64_t n, uint64_t 
     }
 }
 
-struct TablePtr {
-    const ShardDesc *p;
-    __device__ inline ShardDesc get(uint32_t s) const { return p[s]; }
-};
 struct TableInline {
     InlineShardTable t;
     __device__ inline ShardDesc get(uint32_t s) const { return t.d[s]; }
@@ -246,35 +242,7 @@ __global__ __launch_bounds__(256) void decode_tiled_kernel(Table tab, int total_
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int cell = blockIdx.x * 4 + wave;
     if (cell >= total_cells) return;   // whole wave; no workgroup barrier is used
-    // cells per sub-block of a shard: [3dh x d], [d x dh], [f x d], [d x f]
-    const int c_qkv = (3 * dh / 32) * (d / 64), c_o = (d / 32) * (dh / 64);
-    const int c_1 = (f / 32) * (d / 64), c_2 = (d / 32) * (f / 64);
-    const int per_shard = c_qkv + c_o + c_1 + c_2;
-    const int p = cell / per_shard;
-    int c = cell - p * per_shard;
-    int cols;
-    int64_t sub_off;   // element offset of the sub-block inside the shard
-    if (c < c_qkv) { cols = d; sub_off = 0; }
-    else if (c < c_qkv + c_o) { c -= c_qkv; cols = dh; sub_off = (int64_t)3 * dh * d; }
-    else if (c < c_qkv + c_o + c_1) { c -= c_qkv + c_o; cols = d; sub_off = (int64_t)4 * dh * d; }
-    else { c -= c_qkv + c_o + c_1; cols = f; sub_off = (int64_t)4 * dh * d + (int64_t)f * d; }
-    const int tiles = cols >> 6;
-    const int strip = c / tiles, kt = c - strip * tiles;
-    const ShardDesc sd = tab.get(p);
-    const int bits = sd.bits;
-    if (bits <= 6) {
-        if (lane < (1 << bits)) lut[wave][lane] = (uint16_t)f16_bits(sd.codebook[lane]);
-        __builtin_amdgcn_wave_barrier();
-    }
-    const int64_t elem = sub_off + (int64_t)(strip * 32 + (lane & 31)) * cols + kt * 64 + (lane >> 5) * 32;
-    const Raw raw = load_raw_any(bits, (const uint8_t *)sd.data + (elem >> 5) * (bits * 4));
-    half8 fr[4];
-    decode_raw_any(bits, raw, lut[wave], fr);
-    const int64_t wsh = (int64_t)d * (4 * dh + 2 * f);
-    uint8_t *cell_out = out + ((int64_t)p * wsh + sub_off) * 2 + tiled_cell_offset(strip, kt, cols);
-#pragma unroll
-    for (int q = 0; q < 4; ++q)
-        *((u32x4 *)(cell_out + q * 1024) + lane) = __builtin_bit_cast(u32x4, fr[q]);
+    decode_tiled_cell(tab, cell, d, dh, f, out, lut[wave], lane);
 }
 
 }  // namespace

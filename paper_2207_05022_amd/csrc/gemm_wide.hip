@@ -72,6 +72,7 @@ namespace sti {
 namespace {
 
 constexpr int BK = 64;   // K positions per LDS stage
+constexpr int kComputeUnits = 256;
 constexpr int kGroupRows = 8;   // row tiles per band of the tile order ...
 constexpr int kRowMajorColumnTiles = 12;   // ... used beyond this many column tiles
 
@@ -117,6 +118,63 @@ constexpr size_t wide_lds_bytes()
     constexpr size_t partial = (size_t)(KS - 1) * (RA * 32) * (NW * 32) * 4;
     constexpr size_t m = stages > tile ? stages : tile;
     return m > partial ? m : partial;
+}
+
+// Workgroups of a GEMM_QKV_ATTN launch beyond those of its tiles: the launch has one 128 x 384 tile per
+// sequence and pair of heads (192 for 32 sequences of BERT-base), fewer than the chip has compute
+// units, and a workgroup of this kernel fills a unit, so these land on the units the tiles leave idle.
+// They decompress the next layer's shards into its working buffer (Section "Submodel execution": the
+// next layer is made ready while the current one computes) - work that is bound by memory latency and
+// bandwidth, beside a projection that is bound by the matrix cores.
+// All waves of the workgroup come here.  LDS: the binary16 codebooks, bitwidths and data pointers of all
+// shards first, so that a cell costs one round trip to memory; a wave keeps two cells in flight.
+constexpr size_t kNextDecodeLdsBytes = (size_t)kMaxShardsPerLayer * (kLutEntries * 2 + 4 + 8);
+
+template <int NWAVES>
+__device__ inline void decode_next_layer(const GemmProblem &p, int d, unsigned char *smem, int worker)
+{
+    uint16_t *luts = (uint16_t *)smem;                                                    // [shards][64]
+    int32_t *bits_of = (int32_t *)(smem + (size_t)kMaxShardsPerLayer * kLutEntries * 2);  // [shards]
+    uint64_t *data_of = (uint64_t *)(smem + (size_t)kMaxShardsPerLayer * (kLutEntries * 2 + 4));
+    // (pointers that come out of memory are taken as global-memory pointers by hand: the compiler would
+    //  address through them with the slower flat instructions)
+    auto as_global = [](uint64_t a) { return (const void *)(global_cptr *)a; };
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    for (int s = wave; s < p.next_shards; s += NWAVES) {
+        const ShardDesc sd = p.next_table[s];
+        if (lane == 0) {
+            bits_of[s] = sd.bits;
+            data_of[s] = (uint64_t)sd.data;
+        }
+        if (sd.bits <= 6 && lane < (1 << sd.bits))
+            luts[s * kLutEntries + lane] = (uint16_t)f16_bits(((const float *)as_global((uint64_t)sd.codebook))[lane]);
+    }
+    __syncthreads();
+    const int dh = p.d_head, f = p.next_ffn_per_shard;
+    const int total = (int)((int64_t)d * (4 * dh + 2 * f) / 2048) * p.next_shards;
+    const int stride = p.next_workgroups * NWAVES;
+    int cell = worker * NWAVES + wave;
+    if (cell >= total) return;
+    TiledCell t = locate_tiled_cell(cell, d, dh, f);
+    int bits = bits_of[t.shard];
+    Raw raw = load_tiled_cell_raw(t, bits, as_global(data_of[t.shard]), lane);
+    for (;;) {
+        const int next = cell + stride;
+        TiledCell tn = t;
+        int bits_n = bits;
+        Raw raw_n = raw;
+        if (next < total) {   // (asked for before the current cell is decoded)
+            tn = locate_tiled_cell(next, d, dh, f);
+            bits_n = bits_of[tn.shard];
+            raw_n = load_tiled_cell_raw(tn, bits_n, as_global(data_of[tn.shard]), lane);
+        }
+        half8 fr[4];
+        decode_raw_any(bits, raw, luts + t.shard * kLutEntries, fr);
+        store_tiled_cell(t, d, dh, f, fr, (uint8_t *)p.next_out, lane);
+        if (next >= total) break;
+        cell = next; t = tn; bits = bits_n; raw = raw_n;
+    }
 }
 
 // KS = 2 (outputs as narrow as d_model, long K): the workgroup has two groups of NW waves that
@@ -172,6 +230,12 @@ __global__ __launch_bounds__(NW * KS * 64, 3) void gemm_wide_kernel(
     const int total_tiles = n_tiles * m_tiles;
     const int per_xcd = (total_tiles + 7) / 8;
     const int tile = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if constexpr (KIND == GEMM_QKV_ATTN) {
+        if ((int)(blockIdx.x >> 3) >= per_xcd) {   // behind the tiles' workgroups: the next layer's decompression
+            if (p.next_workgroups > 0) decode_next_layer<NW * KS>(p, hot_block_cols, smem_raw, (int)blockIdx.x - 8 * per_xcd);
+            return;
+        }
+    }
     if ((int)(blockIdx.x >> 3) >= per_xcd || tile >= total_tiles) return;
     const int group = n_tiles > kRowMajorColumnTiles ? kGroupRows : 1;
     const int band = tile / (group * n_tiles);
@@ -568,6 +632,14 @@ hipError_t launch_variant(const GemmProblem &p, const GemmBlocks &blocks, int N,
     const int total = ((N + BN - 1) / BN) * ((p.T + BM - 1) / BM);
     const bool n_split = (KIND == GEMM_QKV || KIND == GEMM_FFN_UP || KIND == GEMM_QKV_ATTN);
     dim3 grid(((total + 7) / 8) * 8, (!n_split && p.k_splits > 1) ? p.k_splits : 1);
+    if (KIND == GEMM_QKV_ATTN && p.next_workgroups > 0) {
+        static_assert(KIND != GEMM_QKV_ATTN || kNextDecodeLdsBytes <= lds, "the decompressing workgroups' tables fit");
+        if (!p.next_table || !p.next_out || p.next_shards <= 0 || p.next_shards > kMaxShardsPerLayer ||
+            p.next_ffn_per_shard <= 0 || p.next_ffn_per_shard % 64 || p.block_cols % 64 ||
+            (int)grid.x + p.next_workgroups > kComputeUnits)
+            return hipErrorInvalidValue;
+        grid.x += p.next_workgroups;
+    }
     const int64_t w_stride = p.n_blocks > 1 ? (const uint8_t *)blocks.b[1].w - (const uint8_t *)blocks.b[0].w : 0;
     launch((gemm_wide_kernel<KIND, RA, NW, KS, EARLY>), grid, dim3(NW * KS * 64), lds, stream, p.A, blocks.b[0].w,
            p.resid, p.bias0, (int32_t)w_stride, p.T, p.lda, p.ldr, (uint32_t)p.block_rows | (uint32_t)p.block_cols << 16,
@@ -592,7 +664,6 @@ struct Shape {
     int ra, nw;
 };
 constexpr Shape kShapes[] = {{4, 12}, {4, 9}, {2, 12}, {2, 6}};
-constexpr int kComputeUnits = 256;
 constexpr int kWaveSlots = 12;   // waves a compute unit holds at this kernel's register budget
 
 }  // namespace
@@ -691,6 +762,15 @@ int gemm_wide_max_k_splits(int64_t T, int N)
 bool gemm_wide_fuses_attention(int B, int L, int m, int dh)
 {
     return L == ATT_L && dh == ATT_DH && m > 0 && (int64_t)B * ((m + 1) / 2) >= kComputeUnits / 2;
+}
+
+// Every workgroup of the launch, tiles and decompression, has a compute unit of its own (one round);
+// below an eighth of the chip the decompression would outlast the projection.
+int gemm_wide_spare_workgroups(int B, int m)
+{
+    const int64_t tiles = (int64_t)B * ((m + 1) / 2);
+    const int64_t spare = kComputeUnits - (tiles + 7) / 8 * 8;
+    return spare >= kComputeUnits / 8 ? (int)spare : 0;
 }
 
 hipError_t launch_gemm_wide(const GemmProblem &p, const GemmBlocks &blocks, hipStream_t stream)

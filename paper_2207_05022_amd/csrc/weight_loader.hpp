@@ -136,6 +136,82 @@ __device__ inline int64_t tiled_cell_offset(int strip, int kt, int cols)
     return ((int64_t)strip * (cols >> 6) + kt) * 4096;
 }
 
+// Cells of the fragment-tiled binary16 working buffer (Section "Submodel execution": the working buffer a
+// layer is decompressed into).  A cell is 32 rows x 64 columns = 4 KiB; cells are numbered shard by shard,
+// and inside a shard over its four sub-blocks [3dh x d], [d x dh], [f x d], [d x f], strip by strip.
+struct TiledCell {
+    int shard;         // index into the run of shards
+    int cols;          // columns of the sub-block
+    int64_t sub_off;   // element offset of the sub-block inside the shard
+    int strip, kt;     // 32-row strip and 64-column tile inside the sub-block
+};
+
+__device__ inline TiledCell locate_tiled_cell(int cell, int d, int dh, int f)
+{
+    const int c_qkv = (3 * dh / 32) * (d / 64), c_o = (d / 32) * (dh / 64);
+    const int c_1 = (f / 32) * (d / 64), c_2 = (d / 32) * (f / 64);
+    const int per_shard = c_qkv + c_o + c_1 + c_2;
+    TiledCell t;
+    t.shard = cell / per_shard;
+    int c = cell - t.shard * per_shard;
+    if (c < c_qkv) { t.cols = d; t.sub_off = 0; }
+    else if (c < c_qkv + c_o) { c -= c_qkv; t.cols = dh; t.sub_off = (int64_t)3 * dh * d; }
+    else if (c < c_qkv + c_o + c_1) { c -= c_qkv + c_o; t.cols = d; t.sub_off = (int64_t)4 * dh * d; }
+    else { c -= c_qkv + c_o + c_1; t.cols = f; t.sub_off = (int64_t)4 * dh * d + (int64_t)f * d; }
+    const int tiles = t.cols >> 6;
+    t.strip = c / tiles;
+    t.kt = c - t.strip * tiles;
+    return t;
+}
+
+// this lane's 32 weights of the cell (row lane % 32, columns (lane / 32) * 32 .. + 32 of the tile), as stored
+__device__ inline Raw load_tiled_cell_raw(const TiledCell &t, int bits, const void *data, int lane)
+{
+    const int64_t elem = t.sub_off + (int64_t)(t.strip * 32 + (lane & 31)) * t.cols + t.kt * 64 + (lane >> 5) * 32;
+    return load_raw_any(bits, (const uint8_t *)data + (elem >> 5) * (bits * 4));
+}
+
+__device__ inline void store_tiled_cell(const TiledCell &t, int d, int dh, int f, const half8 (&fr)[4],
+                                        uint8_t *out, int lane)
+{
+    const int64_t wsh = (int64_t)d * (4 * dh + 2 * f);
+    uint8_t *cell_out = out + ((int64_t)t.shard * wsh + t.sub_off) * 2 + tiled_cell_offset(t.strip, t.kt, t.cols);
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+        *((u32x4 *)(cell_out + q * 1024) + lane) = __builtin_bit_cast(u32x4, fr[q]);
+}
+
+// One wave decodes cell number `cell` into the working buffer at `out`.  lut: 64 entries of LDS that
+// belong to this wave alone.
+template <typename Table>
+__device__ inline void decode_tiled_cell(const Table &tab, int cell, int d, int dh, int f, uint8_t *out,
+                                         uint16_t *lut, int lane)
+{
+    const TiledCell t = locate_tiled_cell(cell, d, dh, f);
+    const ShardDesc sd = tab.get(t.shard);
+    const int bits = sd.bits;
+    if (bits <= 6) {
+        // (LDS serves a wave's accesses in order; the fences keep the compiler from moving this table's
+        //  writes above the reads of the previous cell's table, and its reads above the writes)
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        if (lane < (1 << bits)) lut[lane] = (uint16_t)f16_bits(sd.codebook[lane]);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    }
+    const Raw raw = load_tiled_cell_raw(t, bits, sd.data, lane);
+    half8 fr[4];
+    decode_raw_any(bits, raw, lut, fr);
+    store_tiled_cell(t, d, dh, f, fr, out, lane);
+}
+
+// shard table in device memory
+struct TablePtr {
+    const ShardDesc *p;
+    __device__ inline ShardDesc get(uint32_t s) const { return p[s]; }
+};
+
 // four fragments of one cell for this lane
 __device__ inline Raw load_tiled(const void *cell, int lane)
 {

@@ -402,9 +402,10 @@ def _run_model_route(gpu, wl, nbytes):
 
 def test_mfma_config4_on_the_timed_route_every_sequence(gpu, oracle_mod):
     """Configuration 4 exactly as bench.py times it (Section "Submodel execution": layers in
-    order): 12 layers, a workspace of sti_model_workspace_bytes, hence three decompression groups
-    of four layers with non-zero table and working-buffer offsets, unmasked.  All 32 sequences
-    against the oracle; the bits of the per-layer route."""
+    order): 12 layers, a workspace of sti_model_workspace_bytes, hence a working buffer per layer
+    with non-zero table and buffer offsets; the first layer is decompressed by a launch of its own,
+    every other one by the idle workgroups of the Q/K/V + attention launch before it; unmasked.
+    All 32 sequences against the oracle; the bits of the per-layer route."""
     torch, P, D = gpu
     wl = S.config4()
     prec = P.STI_PREC_F16_MFMA
@@ -421,6 +422,52 @@ def test_mfma_config4_on_the_timed_route_every_sequence(gpu, oracle_mod):
     assert_parity(got, want, TOL["mfma"])
     for b in range(wl.batch):
         assert_parity(got[b], want[b], TOL["mfma"], b)
+
+
+def test_next_layer_decompressed_beside_the_projection_with_outlier_dictionaries(gpu, oracle_mod):
+    """32 sequences of 128 tokens with 9 of 12 shards per layer: the fused Q/K/V + attention launch
+    has 160 tiles (the last pair of heads is half empty), and the whole-model route lets its idle
+    workgroups decompress the following layer (Section "Submodel execution": the next layer is made
+    ready while this one computes); the outlier dictionaries of that layer go in behind the launch.
+    Bits of the per-layer route, oracle on every sequence."""
+    torch, P, D = gpu
+    wl = S.small_workload(515, S.BERT_BASE, 4, 32, 128, n_absent=3, bit_choices=(2, 3, 4, 5, 6, 32), io_dtype="f16")
+    wl = _with_outliers(wl, 17, fraction=0.01)
+    S.make_every_term_matter(wl, 29, amp=2.0)
+    prec = P.STI_PREC_F16_MFMA
+    big = P.sti_model_workspace_bytes(wl.dims, wl.n_layers, wl.batch, wl.seq, prec)
+    small = P.sti_workspace_bytes(wl.dims, wl.batch, wl.seq, prec)
+    rolling = _run_model_route(gpu, wl, big)
+    per_layer = _run_model_route(gpu, wl, small)
+    assert torch.equal(rolling, per_layer)
+    want = oracle_mod.model_forward(wl.dims, wl.shards, wl.params, wl.x)
+    got = rolling.float().cpu().numpy()
+    assert_parity(got, want, TOL["mfma"])
+    for b in range(wl.batch):
+        assert_parity(got[b], want[b], TOL["mfma"], b)
+
+
+def test_layers_that_can_and_cannot_take_the_next_layer_along(gpu, oracle_mod):
+    """38 sequences: a full layer has 228 tiles and no compute unit to spare, a layer with 9 or 10 shards
+    190 tiles and 64; with an all-absent layer in between.  Layers 0 to 3 are decompressed as a group,
+    layer 3 takes layer 4 along, layer 5 is decompressed alone."""
+    torch, P, D = gpu
+    rng = np.random.default_rng(77)
+    plan = rng.choice([2, 3, 4, 5, 6, 32], size=(6, 12)).astype(np.int8)
+    plan[1, [2, 7]] = 0
+    plan[2, :] = 0
+    plan[3, [0, 5, 11]] = 0
+    plan[5, [4, 9]] = 0
+    wl = S.small_workload(616, S.BERT_BASE, 6, 38, 128, plan=plan, io_dtype="f16")
+    wl = _with_outliers(wl, 19, fraction=0.005)
+    prec = P.STI_PREC_F16_MFMA
+    big = P.sti_model_workspace_bytes(wl.dims, wl.n_layers, wl.batch, wl.seq, prec)
+    small = P.sti_workspace_bytes(wl.dims, wl.batch, wl.seq, prec)
+    mixed = _run_model_route(gpu, wl, big)
+    per_layer = _run_model_route(gpu, wl, small)
+    assert torch.equal(mixed, per_layer)
+    want = oracle_mod.model_forward(wl.dims, wl.shards, wl.params, wl.x)
+    assert_parity(mixed.float().cpu().numpy(), want, TOL["mfma"])
 
 
 def test_mfma_one_layer_per_decompression_group_with_outlier_dictionaries(gpu, oracle_mod):
