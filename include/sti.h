@@ -294,8 +294,8 @@ sti_status sti_model_forward_masked(const sti_dims *dims, int n_layers, const st
  * decompressed by one launch right before the first of them runs).  Applies to STI_PREC_F16_MFMA whenever
  * the layer goes through the working buffer (more than 128 tokens, more than 192 when
  * d_model <= 768); otherwise, and for n_layers <= 1, it equals sti_workspace_bytes.
- * sti_model_forward takes the grouped route whenever workspace_bytes is at least this value
- * and the per-layer route otherwise: same results either way.  The grouped route uploads
+ * sti_model_forward takes this whole-model route whenever workspace_bytes is at least this value
+ * and the per-layer route otherwise: same results either way.  The whole-model route uploads
  * a shard table through a pinned host buffer that later calls reuse and is therefore
  * never taken while `hip_stream` is capturing: a captured call runs the per-layer route
  * (kernel launches only), whatever the workspace size.  0 on invalid arguments. */
