@@ -388,14 +388,19 @@ def test_mfma_whole_model_decode_matches_per_layer_route(gpu, oracle_mod):
     assert P.sti_model_workspace_bytes(wl.dims, wl.n_layers, 1, 128, prec) == P.sti_workspace_bytes(wl.dims, 1, 128, prec)
 
 
-def _run_model_route(gpu, wl, nbytes):
-    """sti_model_forward on the matrix-core path with a workspace of `nbytes`."""
+def _run_model_route(gpu, wl, nbytes, key_lengths=None):
+    """sti_model_forward(_masked) on the matrix-core path with a workspace of `nbytes`."""
     torch, P, D = gpu
     shards, params, xd = D.upload_workload(wl)
     store = P.make_store(D.store_from_plan(shards))
     ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
     y = torch.full_like(xd, float("nan"))
-    P.sti_model_forward(wl.dims, store, params, wl.plan, xd, y, P.STI_PREC_F16_MFMA, ws)
+    if key_lengths is None:
+        P.sti_model_forward(wl.dims, store, params, wl.plan, xd, y, P.STI_PREC_F16_MFMA, ws)
+    else:
+        P.sti_model_forward_masked(wl.dims, store, params, wl.plan, xd, y,
+                                   torch.tensor(key_lengths, dtype=torch.int32, device="cuda"),
+                                   P.STI_PREC_F16_MFMA, ws)
     torch.cuda.synchronize()
     return y
 
@@ -468,6 +473,36 @@ def test_layers_that_can_and_cannot_take_the_next_layer_along(gpu, oracle_mod):
     assert torch.equal(mixed, per_layer)
     want = oracle_mod.model_forward(wl.dims, wl.shards, wl.params, wl.x)
     assert_parity(mixed.float().cpu().numpy(), want, TOL["mfma"])
+
+
+def test_whole_model_route_random_sweep_is_the_per_layer_route(gpu):
+    """Seeded sweep over 128-token batches of 6 to 43 sequences, three shapes, 2 to 5 layers with 0 to all
+    shards absent per layer, with and without outlier dictionaries and key lengths: whichever layers
+    are decompressed by launches of their own or beside their predecessor's projection, the whole-model
+    route gives the bits of the per-layer route (which the other tests hold against the oracle)."""
+    torch, P, D = gpu
+    prec = P.STI_PREC_F16_MFMA
+    rng = np.random.default_rng(2024)
+    shapes = [S.BERT_BASE, S.Dims(512, 8, 64, 256, 1e-12), S.Dims(1024, 16, 64, 256, 1e-12)]
+    for it in range(18):
+        dims = shapes[it % 3]
+        M = dims.n_heads
+        n_layers = int(rng.integers(2, 6))
+        B = int(rng.integers(6, 44))
+        plan = rng.choice([2, 3, 4, 5, 6, 32], size=(n_layers, M)).astype(np.int8)
+        for l in range(n_layers):
+            k = int(rng.integers(0, M + 1)) if rng.random() < 0.15 else int(rng.integers(0, 5))
+            plan[l, rng.choice(M, k, replace=False)] = 0
+        wl = S.small_workload(9000 + it, dims, n_layers, B, 128, plan=plan, io_dtype="f16")
+        if it % 2:
+            wl = _with_outliers(wl, it, fraction=0.003)
+        lengths = rng.integers(1, 129, size=B).astype(np.int32) if it % 4 == 3 else None
+        big = P.sti_model_workspace_bytes(dims, n_layers, B, 128, prec)
+        small = P.sti_workspace_bytes(dims, B, 128, prec)
+        whole = _run_model_route(gpu, wl, big, key_lengths=lengths)
+        per_layer = _run_model_route(gpu, wl, small, key_lengths=lengths)
+        assert torch.equal(whole, per_layer), (it, dims.d_model, B, [int((plan[l] != 0).sum()) for l in range(n_layers)])
+        assert torch.isfinite(whole.float()).all()
 
 
 def test_mfma_one_layer_per_decompression_group_with_outlier_dictionaries(gpu, oracle_mod):
