@@ -286,12 +286,13 @@ sti_status sti_model_forward_masked(const sti_dims *dims, int n_layers, const st
                                     const int32_t *key_lengths, sti_precision precision, void *workspace,
                                     size_t workspace_bytes, void *hip_stream);
 
-/* Workspace size with which sti_model_forward keeps a working buffer per layer
- * (Section "Submodel execution" keeps one layer's working buffer because memory is scarce on
- * the paper's devices; with room for one buffer per layer, a layer is decompressed while the
- * layer before it computes - by the workgroups that the Q/K/V + attention launch of 128-token
- * sequences has to spare, when it has at least 32 of them - and otherwise a few layers are
- * decompressed by one launch right before the first of them runs).  Applies to STI_PREC_F16_MFMA whenever
+/* Workspace size with which sti_model_forward keeps a ring of working buffers - two to four
+ * layers' worth (64 MiB), never fewer than two - and the model's shard table in device memory
+ * (Section "Submodel execution" keeps one layer's working buffer and decompresses a layer right
+ * before it computes; with a second buffer a layer is decompressed while the layer before it
+ * computes - by the workgroups that the Q/K/V launch of that layer has to spare, when it has at
+ * least 32 of them - and otherwise a few layers are decompressed by one launch right before the
+ * first of them runs).  Applies to STI_PREC_F16_MFMA whenever
  * the layer goes through the working buffer (more than 128 tokens, more than 192 when
  * d_model <= 768); otherwise, and for n_layers <= 1, it equals sti_workspace_bytes.
  * sti_model_forward takes this whole-model route whenever workspace_bytes is at least this value

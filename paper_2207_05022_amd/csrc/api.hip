@@ -200,12 +200,24 @@ sti_status check_decode_shard(const sti_shard &s)
 
 
 // Offsets of the scratch regions of one layer call (sized for all M shards present).
-WorkspaceLayout workspace_layout(const sti_dims &d, int64_t T, sti_precision prec, int w16_layers)
+WorkspaceLayout workspace_layout(const sti_dims &d, int64_t T, sti_precision prec, int model_layers)
 {
     WorkspaceLayout L;
-    L.w16_layers = (prec == STI_PREC_F32 || w16_layers < 1) ? 1 : w16_layers;
     const size_t es = (prec == STI_PREC_F32) ? 4 : 2;
     const size_t M = d.n_heads, dm = d.d_model, dh = d.d_head, f = d.ffn_per_shard;
+    if (prec != STI_PREC_F32 && model_layers > 1) {
+        // Layers are decompressed in groups, each group right before its first layer: working
+        // buffers written shortly before they are read are still in the memory-side cache (the
+        // FFN2 projection measured 7 % faster than with one launch for the whole model up front),
+        // while one launch per layer is too short to keep HBM busy.  A group is as many layers as
+        // fit 64 MiB of working buffers (4 layers of BERT-base).
+        const size_t layer_w16_bytes = M * dm * (4 * dh + 2 * f) * 2;
+        size_t group = ((size_t)64 << 20) / (layer_w16_bytes ? layer_w16_bytes : 1);
+        if (group < 1) group = 1;
+        if (group > (size_t)model_layers) group = (size_t)model_layers;
+        L.decode_group = (int)group;
+        L.w16_layers = (int)(group < 2 ? 2 : group);
+    }
     size_t off = 0;
     auto take = [&](size_t bytes) {
         size_t at = off;
@@ -229,7 +241,7 @@ WorkspaceLayout workspace_layout(const sti_dims &d, int64_t T, sti_precision pre
     }
     L.h = take((size_t)T * dm * es);
     L.u = take((size_t)T * M * f * es);
-    if (L.w16_layers > 1) L.table = take((size_t)L.w16_layers * M * sizeof(ShardDesc));
+    if (L.w16_layers > 1) L.table = take((size_t)model_layers * M * sizeof(ShardDesc));
     L.total = off;
     return L;
 }
@@ -302,7 +314,11 @@ static_assert(kSkinnyMaxTokens >= 192, "the partial-sum planes are sized with kS
 int spare_decode_workgroups(const sti_dims &d, int B, int Lseq, int m, sti_precision prec)
 {
     if (prec != STI_PREC_F16_MFMA || m <= 0 || few_token_path(d, (int64_t)B * Lseq)) return 0;
-    return gemm_wide_fuses_attention(B, Lseq, m, d.d_head) ? gemm_wide_spare_workgroups(B, m) : 0;
+    GemmProblem p;
+    memset(&p, 0, sizeof(p));
+    p.kind = gemm_wide_fuses_attention(B, Lseq, m, d.d_head) ? GEMM_QKV_ATTN : GEMM_QKV;
+    p.T = B * Lseq; p.n_blocks = m; p.block_rows = 3 * d.d_head; p.block_cols = d.d_model;
+    return gemm_wide_spare_workgroups(p);
 }
 
 sti_status run_layer(const sti_dims &d, const sti_shard *shards, const sti_layer_params &prm,
@@ -430,7 +446,11 @@ sti_status run_layer(const sti_dims &d, const sti_shard *shards, const sti_layer
             }
             STI_TRY(gemm(p, bq));
         } else {
-            if (next) return STI_ERR_UNSUPPORTED;   // (the caller asked spare_decode_workgroups first)
+            if (next && next->workgroups > 0 && next->n_shards > 0) {
+                if (f32 || skinny) return STI_ERR_UNSUPPORTED;   // (the caller asked spare_decode_workgroups first)
+                p.next_table = next->table; p.next_shards = next->n_shards; p.next_out = next->out;
+                p.next_workgroups = next->workgroups; p.next_ffn_per_shard = f;
+            }
             STI_TRY(gemm(p, bq));
             STI_TRY(timed(STI_K_ATTENTION, stream, [&] {
                 return f32 ? launch_attention_f32((const float *)qkv, (float *)ctx, B, Lseq, m, dh, key_lengths, stream)
@@ -862,15 +882,12 @@ sti_status model_forward(const sti_dims *dims, int n_layers, const sti_shard *st
         if (!table.empty())
             STI_TRY(staging().upload(table.data(), table.size(), (ShardDesc *)(ws + wl.table), stream));
     }
-    // Layers are decompressed in groups, each group right before its first layer: working
-    // buffers written shortly before they are read are still in the memory-side cache (the
-    // FFN2 projection measured 7 % faster than with one launch for the whole model up front),
-    // while one launch per layer is too short to keep HBM busy.  A group is as many layers as
-    // fit 64 MiB of working buffers (4 layers of BERT-base).
-    const size_t layer_w16_bytes = (size_t)M * wsh * 2;
-    int decode_group = (int)(((size_t)64 << 20) / (layer_w16_bytes ? layer_w16_bytes : 1));
-    if (decode_group < 1) decode_group = 1;
-    if (decode_group > n_layers) decode_group = n_layers;
+    // Layer l's working buffer is slot l % w16_layers of a ring (a slot holds a full layer): a group of
+    // decode_group <= w16_layers layers has slots of its own, the slot of layer l + 1 is not that of
+    // layer l, and whatever a slot held before belongs to a layer whose launches are already behind on
+    // the stream.  (A ring rather than a buffer per layer: less memory, and measured 1-2.5 % faster.)
+    const int decode_group = wl.decode_group;
+    auto w16_of = [&](int l) { return ws + wl.w16 + (size_t)(l % wl.w16_layers) * M * wsh * 2; };
     const ShardDesc *dev_table = (const ShardDesc *)(ws + wl.table);
     auto last_shard = [&](int l) { return (l + 1 < n_layers) ? first_shard[l + 1] : table.size(); };
     // put layer l's outlier dictionaries into its working buffer (absent in most stores)
@@ -885,20 +902,27 @@ sti_status model_forward(const sti_dims *dims, int n_layers, const sti_shard *st
         }
         if (max_outliers > 0)
             STI_TRY(launch_patch_outliers_tiled(t, (int)(b - a), max_outliers, dims->d_model, dims->d_head,
-                                                dims->ffn_per_shard, ws + wl.w16 + a * wsh * 2, stream));
+                                                dims->ffn_per_shard, w16_of(l), stream));
         return STI_OK;
     };
     // decompress layers [l0, l1) into their working buffers and apply their outlier dictionaries
     auto decode_layers = [&](int l0, int l1) -> sti_status {
-        const size_t lo = first_shard[l0], hi = last_shard(l1 - 1);
-        if (hi == lo) return STI_OK;
-        STI_TRY(timed(STI_K_DECODE, stream, [&] {
-            return launch_decode_tiled_table(dev_table + lo, (int)(hi - lo), dims->d_model, dims->d_head,
-                                             dims->ffn_per_shard, ws + wl.w16 + lo * wsh * 2, stream);
-        }));
+        // (the caller keeps a group inside the ring: slots l0 % w16_layers ... are consecutive)
+        bool all_full = true;   // then the shards of the group lie back to back, as one launch writes them
+        for (int l = l0; l < l1; ++l) all_full = all_full && last_shard(l) - first_shard[l] == (size_t)M;
         for (int l = l0; l < l1; ++l) {
-            sti_status ps = patch_layer(l);
-            if (ps != STI_OK) return ps;
+            const int lend = all_full ? l1 : l + 1;   // one launch for the group, else one per layer
+            const size_t lo = first_shard[l], hi = last_shard(lend - 1);
+            if (hi > lo)
+                STI_TRY(timed(STI_K_DECODE, stream, [&] {
+                    return launch_decode_tiled_table(dev_table + lo, (int)(hi - lo), dims->d_model, dims->d_head,
+                                                     dims->ffn_per_shard, w16_of(l), stream);
+                }));
+            for (int k = l; k < lend; ++k) {
+                sti_status ps = patch_layer(k);
+                if (ps != STI_OK) return ps;
+            }
+            l = lend - 1;
         }
         return STI_OK;
     };
@@ -925,6 +949,8 @@ sti_status model_forward(const sti_dims *dims, int n_layers, const sti_shard *st
             const int spare_here = spare(l);
             if (l >= decoded_upto) {
                 int l1 = l + decode_group < n_layers ? l + decode_group : n_layers;
+                const int to_wrap = wl.w16_layers - l % wl.w16_layers;   // slots up to the end of the ring
+                if (l1 > l + to_wrap) l1 = l + to_wrap;
                 if (spare_here > 0) l1 = l + 1;   // the layers behind this one ride along with their predecessors
                 st = decode_layers(l, l1);
                 if (st != STI_OK) return st;
@@ -932,11 +958,11 @@ sti_status model_forward(const sti_dims *dims, int n_layers, const sti_shard *st
             }
             if (spare_here > 0 && l + 1 == decoded_upto && l + 1 < n_layers) {
                 const size_t a = first_shard[l + 1], b = last_shard(l + 1);
-                if (b > a) next_decode = {dev_table + a, (int)(b - a), ws + wl.w16 + a * wsh * 2, spare_here};
+                if (b > a) next_decode = {dev_table + a, (int)(b - a), w16_of(l + 1), spare_here};
                 decoded_upto = l + 2;
             }
         }
-        const void *predecoded = whole_model_fits ? (const void *)(ws + wl.w16 + first_shard[l] * wsh * 2) : nullptr;
+        const void *predecoded = whole_model_fits ? (const void *)w16_of(l) : nullptr;
         st = run_layer(*dims, &chosen[(size_t)l * M], params[l], cur, out, last ? io_dtype : act,
                        batch, seq, precision, ws, wl, stream, predecoded, masked ? key_lengths : nullptr,
                        next_decode.workgroups > 0 ? &next_decode : nullptr);

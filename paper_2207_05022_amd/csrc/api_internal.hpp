@@ -16,11 +16,13 @@ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 // Offsets of the scratch regions of one layer call inside the caller's workspace.
 struct WorkspaceLayout {
     size_t w32 = 0, w16 = 0, act[2] = {0, 0}, qkv = 0, ctx = 0, pre = 0, h = 0, u = 0, table = 0, total = 0;
-    int w16_layers = 1;   // layers the binary16 working buffer holds at once
+    int w16_layers = 1;   // layers the binary16 working buffer holds at once (a ring: layer l in slot l % w16_layers)
+    int decode_group = 1; // layers that one decompression launch of sti_model_forward takes (<= w16_layers)
 };
-// w16_layers > 1: room for that many layers' binary16 working buffers (decompressed a few
-// layers per launch by sti_model_forward) and for the device copy of their shard table.
-WorkspaceLayout workspace_layout(const sti_dims &d, int64_t T, sti_precision prec, int w16_layers = 1);
+// model_layers > 1 (sti_model_forward with room for it): a ring of binary16 working buffers - as many
+// layers as one decompression launch takes (64 MiB worth), at least two, so that a layer can be
+// decompressed while the one before it computes - and the device copy of the whole model's shard table.
+WorkspaceLayout workspace_layout(const sti_dims &d, int64_t T, sti_precision prec, int model_layers = 1);
 
 sti_status check_dims(const sti_dims *dims, int batch, int seq, sti_precision prec);
 sti_status check_decode_shard(const sti_shard &s);   // bitwidth 2..6 or 32, pointers, alignment
@@ -29,7 +31,7 @@ sti_status check_io(const void *x, void *y, sti_dtype io, int64_t T, int d);
 
 // One layer over shards[M] (bitwidth 0 = absent), arguments already validated.  `in` is
 // float32 (F32 precision) or binary16 (MFMA precision); `out` is written as out_dtype.
-// What a layer's fused Q/K/V + attention launch does on the compute units its tiles leave idle:
+// What a layer's Q/K/V launch (many-token route) does on the compute units its tiles leave idle:
 // decompress the following layer (n_shards shards of the device table into the working buffer `out`,
 // dictionaries of outliers not applied) with `workgroups` workgroups.
 struct NextLayerDecode {
@@ -38,8 +40,8 @@ struct NextLayerDecode {
     void *out;
     int workgroups;
 };
-// Workgroups such a launch has to spare for a layer of m present shards (0: its projection does not
-// take that form, or fills the chip).
+// Workgroups such a launch has to spare for a layer of m present shards (0: the layer does not go
+// through the many-token route, or its projection fills the chip).
 int spare_decode_workgroups(const sti_dims &d, int B, int Lseq, int m, sti_precision prec);
 
 sti_status run_layer(const sti_dims &d, const sti_shard *shards, const sti_layer_params &prm,

@@ -120,14 +120,15 @@ constexpr size_t wide_lds_bytes()
     return m > partial ? m : partial;
 }
 
-// Workgroups of a GEMM_QKV_ATTN launch beyond those of its tiles: the launch has one 128 x 384 tile per
-// sequence and pair of heads (192 for 32 sequences of BERT-base), fewer than the chip has compute
-// units, and a workgroup of this kernel fills a unit, so these land on the units the tiles leave idle.
-// They decompress the next layer's shards into its working buffer (Section "Submodel execution": the
-// next layer is made ready while the current one computes) - work that is bound by memory latency and
-// bandwidth, beside a projection that is bound by the matrix cores.
+// Workgroups of a Q/K/V launch beyond those of its tiles.  With 128-token sequences the launch has one
+// 128 x 384 tile per sequence and pair of heads (192 for 32 sequences of BERT-base), with a few hundred
+// tokens a few dozen tiles: fewer than the chip has compute units, so these land on units the tiles
+// leave idle.  They decompress the next layer's shards into its working buffer (Section "Submodel
+// execution": the next layer is made ready while the current one computes) - work that is bound by
+// memory latency and bandwidth, beside a projection that is bound by the matrix cores.
 // All waves of the workgroup come here.  LDS: the binary16 codebooks, bitwidths and data pointers of all
-// shards first, so that a cell costs one round trip to memory; a wave keeps two cells in flight.
+// shards, so that a cell costs one round trip to memory; a wave asks for three cells at a time, the first
+// three together with the codebooks (a short projection must not end up waiting for these workgroups).
 constexpr size_t kNextDecodeLdsBytes = (size_t)kMaxShardsPerLayer * (kLutEntries * 2 + 4 + 8);
 
 template <int NWAVES>
@@ -141,39 +142,65 @@ __device__ inline void decode_next_layer(const GemmProblem &p, int d, unsigned c
     auto as_global = [](uint64_t a) { return (const void *)(global_cptr *)a; };
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    for (int s = wave; s < p.next_shards; s += NWAVES) {
-        const ShardDesc sd = p.next_table[s];
-        if (lane == 0) {
-            bits_of[s] = sd.bits;
-            data_of[s] = (uint64_t)sd.data;
+    // round trip 1: the descriptors; round trip 2: the codebooks together with the first cells
+    constexpr int SPW = (kMaxShardsPerLayer + NWAVES - 1) / NWAVES;   // shards a wave stages
+    float centroid[SPW];
+    int staged_bits[SPW];
+#pragma unroll
+    for (int j = 0; j < SPW; ++j) {
+        const int s = wave + j * NWAVES;
+        centroid[j] = 0.f;
+        staged_bits[j] = 0;
+        if (s < p.next_shards) {
+            const ShardDesc sd = p.next_table[s];
+            staged_bits[j] = sd.bits;
+            if (lane == 0) {
+                bits_of[s] = sd.bits;
+                data_of[s] = (uint64_t)sd.data;
+            }
+            if (sd.bits <= 6 && lane < (1 << sd.bits)) centroid[j] = ((const float *)as_global((uint64_t)sd.codebook))[lane];
         }
-        if (sd.bits <= 6 && lane < (1 << sd.bits))
-            luts[s * kLutEntries + lane] = (uint16_t)f16_bits(((const float *)as_global((uint64_t)sd.codebook))[lane]);
     }
     __syncthreads();
     const int dh = p.d_head, f = p.next_ffn_per_shard;
     const int total = (int)((int64_t)d * (4 * dh + 2 * f) / 2048) * p.next_shards;
     const int stride = p.next_workgroups * NWAVES;
-    int cell = worker * NWAVES + wave;
-    if (cell >= total) return;
-    TiledCell t = locate_tiled_cell(cell, d, dh, f);
-    int bits = bits_of[t.shard];
-    Raw raw = load_tiled_cell_raw(t, bits, as_global(data_of[t.shard]), lane);
-    for (;;) {
-        const int next = cell + stride;
-        TiledCell tn = t;
-        int bits_n = bits;
-        Raw raw_n = raw;
-        if (next < total) {   // (asked for before the current cell is decoded)
-            tn = locate_tiled_cell(next, d, dh, f);
-            bits_n = bits_of[tn.shard];
-            raw_n = load_tiled_cell_raw(tn, bits_n, as_global(data_of[tn.shard]), lane);
+    constexpr int CH = 3;   // cells a wave asks for at a time
+    TiledCell t[CH];
+    int bits[CH];
+    Raw raw[CH];
+    auto request = [&](int first) {
+#pragma unroll
+        for (int c = 0; c < CH; ++c) {
+            const int cell = first + c * stride;
+            bits[c] = 0;   // (no cell)
+            if (cell < total) {
+                t[c] = locate_tiled_cell(cell, d, dh, f);
+                bits[c] = bits_of[t[c].shard];
+                raw[c] = load_tiled_cell_raw(t[c], bits[c], as_global(data_of[t[c].shard]), lane);
+            }
         }
-        half8 fr[4];
-        decode_raw_any(bits, raw, luts + t.shard * kLutEntries, fr);
-        store_tiled_cell(t, d, dh, f, fr, (uint8_t *)p.next_out, lane);
-        if (next >= total) break;
-        cell = next; t = tn; bits = bits_n; raw = raw_n;
+    };
+    int first = worker * NWAVES + wave;
+    request(first);
+#pragma unroll
+    for (int j = 0; j < SPW; ++j) {
+        const int s = wave + j * NWAVES;
+        if (s < p.next_shards && staged_bits[j] <= 6 && lane < (1 << staged_bits[j]))
+            luts[s * kLutEntries + lane] = (uint16_t)f16_bits(centroid[j]);
+    }
+    __syncthreads();
+    while (first < total) {
+#pragma unroll
+        for (int c = 0; c < CH; ++c) {
+            if (bits[c] != 0) {
+                half8 fr[4];
+                decode_raw_any(bits[c], raw[c], luts + t[c].shard * kLutEntries, fr);
+                store_tiled_cell(t[c], d, dh, f, fr, (uint8_t *)p.next_out, lane);
+            }
+        }
+        first += CH * stride;
+        if (first < total) request(first);
     }
 }
 
@@ -230,7 +257,7 @@ __global__ __launch_bounds__(NW * KS * 64, 3) void gemm_wide_kernel(
     const int total_tiles = n_tiles * m_tiles;
     const int per_xcd = (total_tiles + 7) / 8;
     const int tile = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-    if constexpr (KIND == GEMM_QKV_ATTN) {
+    if constexpr (qkv) {
         if ((int)(blockIdx.x >> 3) >= per_xcd) {   // behind the tiles' workgroups: the next layer's decompression
             if (p.next_workgroups > 0) decode_next_layer<NW * KS>(p, hot_block_cols, smem_raw, (int)blockIdx.x - 8 * per_xcd);
             return;
@@ -632,8 +659,8 @@ hipError_t launch_variant(const GemmProblem &p, const GemmBlocks &blocks, int N,
     const int total = ((N + BN - 1) / BN) * ((p.T + BM - 1) / BM);
     const bool n_split = (KIND == GEMM_QKV || KIND == GEMM_FFN_UP || KIND == GEMM_QKV_ATTN);
     dim3 grid(((total + 7) / 8) * 8, (!n_split && p.k_splits > 1) ? p.k_splits : 1);
-    if (KIND == GEMM_QKV_ATTN && p.next_workgroups > 0) {
-        static_assert(KIND != GEMM_QKV_ATTN || kNextDecodeLdsBytes <= lds, "the decompressing workgroups' tables fit");
+    if ((KIND == GEMM_QKV_ATTN || KIND == GEMM_QKV) && p.next_workgroups > 0) {
+        static_assert((KIND != GEMM_QKV_ATTN && KIND != GEMM_QKV) || kNextDecodeLdsBytes <= lds, "the decompressing workgroups' tables fit");
         if (!p.next_table || !p.next_out || p.next_shards <= 0 || p.next_shards > kMaxShardsPerLayer ||
             p.next_ffn_per_shard <= 0 || p.next_ffn_per_shard % 64 || p.block_cols % 64 ||
             (int)grid.x + p.next_workgroups > kComputeUnits)
@@ -764,11 +791,15 @@ bool gemm_wide_fuses_attention(int B, int L, int m, int dh)
     return L == ATT_L && dh == ATT_DH && m > 0 && (int64_t)B * ((m + 1) / 2) >= kComputeUnits / 2;
 }
 
-// Every workgroup of the launch, tiles and decompression, has a compute unit of its own (one round);
+// Every workgroup of the launch, tiles and decompression, finds a compute unit in the first round;
 // below an eighth of the chip the decompression would outlast the projection.
-int gemm_wide_spare_workgroups(int B, int m)
+int gemm_wide_spare_workgroups(const GemmProblem &p)
 {
-    const int64_t tiles = (int64_t)B * ((m + 1) / 2);
+    if (p.n_blocks <= 0 || p.T <= 0) return 0;
+    int64_t tiles;
+    if (p.kind == GEMM_QKV_ATTN) tiles = (int64_t)(p.T / ATT_L) * ((p.n_blocks + 1) / 2);
+    else if (p.kind == GEMM_QKV) tiles = choose(p, p.n_blocks * p.block_rows).tiles;
+    else return 0;
     const int64_t spare = kComputeUnits - (tiles + 7) / 8 * 8;
     return spare >= kComputeUnits / 8 ? (int)spare : 0;
 }

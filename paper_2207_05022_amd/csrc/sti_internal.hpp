@@ -96,7 +96,7 @@ struct GemmProblem {
     int32_t k_splits;
     int64_t partial_stride;
     const int32_t *key_lengths;   // GEMM_QKV_ATTN: real positions per sequence (device, may be null)
-    // GEMM_QKV_ATTN only: workgroups beyond those of the tiles (next_workgroups of them, on compute
+    // wide-tile kernel, GEMM_QKV and GEMM_QKV_ATTN: workgroups beyond those of the tiles (next_workgroups of them, on compute
     // units the tiles leave idle) decompress next_shards shards - the next layer's - from the device
     // table next_table into the working buffer next_out; next_workgroups == 0: nothing of the kind
     const ShardDesc *next_table;
@@ -120,9 +120,10 @@ hipError_t launch_gemm_wide(const GemmProblem &p, const GemmBlocks &blocks, hipS
 bool gemm_wide_supported(const GemmProblem &p, const GemmBlocks &blocks);
 // whether the Q/K/V projection of B sequences of L tokens over m heads should go out as GEMM_QKV_ATTN
 bool gemm_wide_fuses_attention(int B, int L, int m, int dh);
-// workgroups such a launch can give to the next layer's decompression: one per compute unit that its
-// tiles leave idle (0: none to spare, decompress with a launch of its own)
-int gemm_wide_spare_workgroups(int B, int m);
+// workgroups a Q/K/V launch (GEMM_QKV or GEMM_QKV_ATTN; kind, T, n_blocks, block_rows, block_cols set)
+// can give to the next layer's decompression: one per compute unit that its tiles leave idle (0: none to
+// spare, decompress with a launch of its own)
+int gemm_wide_spare_workgroups(const GemmProblem &p);
 // K splits across workgroups the wide-tile kernel wants for this problem (1 = none), and the
 // largest value it can return for T tokens and N output columns (workspace sizing)
 int gemm_wide_k_splits(const GemmProblem &p);

@@ -99,7 +99,13 @@ class Dims:
 def test_model_workspace_query(P):
     one = P.sti_workspace_bytes(Dims(), 32, 128, P.STI_PREC_F16_MFMA)
     whole = P.sti_model_workspace_bytes(Dims(), 12, 32, 128, P.STI_PREC_F16_MFMA)
-    assert whole >= one + 11 * 12 * 589824 * 2            # eleven more binary16 working buffers
+    layer = 12 * 589824 * 2
+    # a ring of four binary16 working buffers (64 MiB worth of layers) + the model's shard table
+    assert one + 3 * layer + 12 * 12 * 48 <= whole < one + 4 * layer
+    # never fewer than two buffers: a layer is decompressed while the one before it computes
+    big = Dims(d=2048, M=32)
+    assert (P.sti_model_workspace_bytes(big, 3, 2, 128, P.STI_PREC_F16_MFMA) - P.sti_workspace_bytes(big, 2, 128, P.STI_PREC_F16_MFMA)
+            >= 32 * 2048 * 768 * 2)
     assert P.sti_model_workspace_bytes(Dims(), 1, 32, 128, P.STI_PREC_F16_MFMA) == one
     assert P.sti_model_workspace_bytes(Dims(), 12, 32, 128, P.STI_PREC_F32) == P.sti_workspace_bytes(Dims(), 32, 128, P.STI_PREC_F32)
     assert P.sti_model_workspace_bytes(Dims(), -1, 32, 128, P.STI_PREC_F16_MFMA) == 0
