@@ -30,10 +30,10 @@ sys.path.insert(0, ROOT)
 TRAFFIC = {
     "gemm": {"files": ("gemm_wide.hip", "attention_core.hpp", "weight_loader.hpp", "sti_internal.hpp"),
              "sha256": "8949c4b33f5dd01a86878197acbb80d4d8d1104a7d7ae490a31041f1e3cdd6b4",
-             "bytes_per_launch": 58889680},
+             "bytes_per_launch": 58889559},
     "decode": {"files": ("decode.hip", "weight_loader.hpp", "sti_internal.hpp"),
                "sha256": "7c03c917b13cf37b695d0f4f52d3fbdf7feaa160de9b1c72985b0183cafc7896",
-               "bytes_per_launch": 6089413575},
+               "bytes_per_launch": 6089426482},
 }
 
 
@@ -458,8 +458,8 @@ def cpu_baselines(S, wl, y, ds):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--print-source-hashes", action="store_true",
                     help="print the kernel source hashes that TRAFFIC is keyed on and exit")
